@@ -1,0 +1,185 @@
+/*
+ * kvx -- compressed-KV streaming attention step for frame-wise causal global
+ * attention (XStreamVGGT, arxiv 2601.01204), hand-written HIP for gfx950.
+ *
+ * One kv_step() is one frame on one per-layer cache:
+ *   1. attention of the frame's queries over [de-quantised cache ; the frame's own
+ *      K/V at input precision]                       (paper Sec. 3.1 Eq. 1, Sec. 3.3 Eq. 10)
+ *   2. append the frame; if the length now exceeds the budget L_max, score the
+ *      middle tokens with the pooled query           (Sec. 3.2 Eq. 2-6)
+ *   3. keep first frame + top-k middle + current frame, k = L_max - 2n, in
+ *      ascending position order                      (Sec. 3.2, keep set)
+ *   4. quantise the final cache: keys per channel over groups of k_group
+ *      consecutive cache tokens, values per token over groups of v_group
+ *      channels, asymmetric uniform, round-to-nearest-even   (Sec. 3.3 Eq. 7-9)
+ *
+ * All pointers named "device" are HIP device pointers on the current device;
+ * "host" pointers are ordinary host memory.  The library owns the cache, the
+ * caller owns q/k/v/out.  No call throws or aborts; every call returns a
+ * kv_status (0 = ok, negative = error) and kv_last_error() gives the text.
+ * A handle is not thread-safe.  Steps on one cache must be stream-ordered.
+ */
+#ifndef KVX_H
+#define KVX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum kv_status {
+  KV_OK = 0,
+  KV_E_INVAL = -1,   /* bad argument or configuration                     */
+  KV_E_NOMEM = -2,   /* device or host allocation failed                  */
+  KV_E_RANGE = -3,   /* stream / layer / size out of range                */
+  KV_E_STATE = -4,   /* call not valid in the handle's current state      */
+  KV_E_HIP = -5      /* a HIP runtime call failed                         */
+};
+
+enum kv_dtype { KV_BF16 = 0, KV_F32 = 1 };
+
+enum kv_mode {
+  KV_COMPRESSED = 0,        /* pruned + quantised cache (the paper's method)                */
+  KV_UNCOMPRESSED_BF16 = 1  /* baseline: bf16 cache that grows by n tokens per frame,       */
+                            /* no pruning, no quantisation (what the paper compares against) */
+};
+
+typedef struct kv_config {
+  int32_t n_streams;        /* independent caches: n_streams x n_layers                        */
+  int32_t n_layers;
+  int32_t n_heads;          /* H                                                               */
+  int32_t head_dim;         /* d; must be 64                                                   */
+  int32_t tokens_per_frame; /* n = 1 + R + N, special tokens first (Sec. 3.1)                  */
+  int32_t n_special;        /* 1 + R camera/register tokens, not pooled (Sec. 3.2 Eq. 2)       */
+  int32_t pool_group;       /* g, patch tokens averaged per pooled query row; paper: 16        */
+  int32_t budget_tokens;    /* L_max; must be >= 2 * tokens_per_frame                          */
+  int32_t k_bits;           /* 2, 4 or 8                                                       */
+  int32_t k_group;          /* tokens per per-channel key group: 32 or 64                      */
+  int32_t v_bits;           /* 2, 4 or 8                                                       */
+  int32_t v_group;          /* channels per per-token value group: 32 or 64                    */
+  int32_t in_dtype;         /* kv_dtype of q, k and v                                          */
+  int32_t out_dtype;        /* kv_dtype of out (fp32 keeps the full result of the fp32         */
+                            /* accumulation; bf16 rounds it to nearest-even on the store)      */
+  int32_t mode;             /* kv_mode                                                         */
+  int32_t max_frames;       /* KV_UNCOMPRESSED_BF16 only: frames the cache is sized for        */
+  float softmax_scale;      /* 0 -> 1/sqrt(head_dim)                                           */
+} kv_config;
+
+typedef struct kv_handle kv_handle;
+
+/* One frame for one cache in a batched call. q, k, v, out: device, [n, H, d] with the
+ * strides given to kv_step_batched. */
+typedef struct kv_step_item {
+  int32_t stream;
+  int32_t layer;
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+} kv_step_item;
+
+typedef struct kv_stats_t {
+  int64_t bytes_allocated;       /* device bytes held by the handle; constant after kv_init      */
+  int64_t bytes_k_codes;         /* of which: key codes (both halves of the double buffer)       */
+  int64_t bytes_k_meta;          /*           key scales and zero-points                         */
+  int64_t bytes_v_codes;
+  int64_t bytes_v_meta;
+  int64_t bytes_ids;
+  int64_t bytes_scratch;         /* attention partials, scores, keep lists                       */
+  int64_t bytes_live_per_cache;  /* codes + metadata of one cache at its current maximum length  */
+  int64_t frames_seen_total;     /* sum over caches                                              */
+  int64_t tokens_dropped_total;  /* sum over caches                                              */
+  int64_t k_groups_rebuilt_total;/* key groups written by the re-quantiser, sum over caches      */
+  int32_t cache_len_min;         /* over caches                                                  */
+  int32_t cache_len_max;
+  int32_t n_caches;
+  int32_t reserved;
+} kv_stats_t;
+
+/* Host buffers for kv_export; any pointer may be NULL to skip that part. Sizes are in
+ * elements, for T = cache length, H heads, d head_dim. */
+typedef struct kv_export_t {
+  int32_t cache_len;     /* out: T                                                            */
+  int32_t frames_seen;   /* out                                                               */
+  int32_t last_keep_len; /* out: length of the last keep list (0 if the last step kept all)   */
+  int32_t last_scores_len; /* out: number of middle tokens scored in the last step            */
+  int32_t* ids;          /* [T] token ids (frame * n + index) in cache order                  */
+  uint8_t* k_codes;      /* [H, T, d] one code per byte                                       */
+  float* k_scale;        /* [H, ceil(T / k_group), d]                                         */
+  int32_t* k_zero;       /* [H, ceil(T / k_group), d]                                         */
+  uint8_t* v_codes;      /* [H, T, d]                                                         */
+  float* v_scale;        /* [H, T, d / v_group]                                               */
+  int32_t* v_zero;       /* [H, T, d / v_group]                                               */
+  int32_t* last_keep;    /* [budget] positions kept by the last pruning step, ascending,      */
+                         /* indexing the pre-prune sequence [cache ; current frame]           */
+  float* last_scores;    /* [last_scores_len] importance scores of the middle tokens          */
+  int32_t capacity_tokens; /* in: capacity of the buffers above in tokens (>= T)              */
+} kv_export_t;
+
+/* Validate the configuration and allocate every device buffer the handle will ever use
+ * (Sec. 3.2: the cache is bounded by L_max, so the footprint is fixed here).
+ * cfg: host. out: host, receives the handle. */
+int kv_init(const kv_config* cfg, kv_handle** out);
+
+/* One frame on cache (stream, layer): Eq. 1 with Eq. 10 inside, then Eq. 2-9 to update
+ * the cache.  q, k, v: device, [n, H, d], element (i, h, c) at i * tok_stride +
+ * h * head_stride + c (strides in elements; the innermost d elements contiguous, every
+ * row 16-byte aligned).  out: device, same layout with the same element strides, in the
+ * configured out_dtype, receives the attention
+ * output defined by the cache as it was before this step's pruning.  Work is enqueued on
+ * hip_stream (a hipStream_t, NULL = default stream); the call never synchronises.  All
+ * validation precedes the first launch, so a failed call leaves the cache unchanged. */
+int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v,
+            int64_t tok_stride, int64_t head_stride, void* out, void* hip_stream);
+
+/* The same for n_items distinct caches in one set of launches (independent streams, or
+ * independent layers of a synthetic stack).  items: host array. */
+int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride,
+                    int64_t head_stride, void* hip_stream);
+
+/* Counters and footprint.  stats: host.  Synchronises the device. */
+int kv_stats(kv_handle* h, kv_stats_t* stats);
+
+/* Copy one cache to host buffers with codes unpacked (parity checks, checkpoints).
+ * Synchronises the device.  bufs: host struct of host pointers. */
+int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* bufs);
+
+/* Forget the contents of one cache (stream, layer), or of all with stream = layer = -1. */
+int kv_reset(kv_handle* h, int32_t stream, int32_t layer);
+
+/* Free everything.  NULL is allowed. */
+void kv_destroy(kv_handle* h);
+
+/* Text of the last error on this handle (or of the last failed kv_init when h is NULL).
+ * The string is owned by the library and valid until the next call. */
+const char* kv_last_error(kv_handle* h);
+
+/* Launch classes of a step, for kv_set_timing / kv_read_timing. */
+enum kv_kernel_id {
+  KV_K_ATTENTION = 0, /* fused de-quantise + attention (Eq. 1, Eq. 10)          */
+  KV_K_COMBINE = 1,   /* merge of the split-KV partial results                   */
+  KV_K_POOL = 2,      /* pooled query (Eq. 2-3 and the row mean of Eq. 6)        */
+  KV_K_SCORE = 3,     /* per-head q~ . K~ over the cached tokens (Eq. 4-5)       */
+  KV_K_SELECT = 4,    /* head sum, top-k, keep list                              */
+  KV_K_REBUILD_K = 5, /* compaction + per-channel key (re)quantisation (Eq. 7-9) */
+  KV_K_REBUILD_V = 6, /* value carry / per-token quantisation, token ids         */
+  KV_K_COUNT = 7
+};
+
+/* Measurement aid: while bit (1 << id) of kernel_mask is set, every launch of that class
+ * is bracketed by HIP events recorded on the stream it runs on.  kv_read_timing waits
+ * for the recorded events, writes per class the summed duration in milliseconds and the
+ * number of launches (host arrays of KV_K_COUNT entries) and clears the record. */
+int kv_set_timing(kv_handle* h, uint32_t kernel_mask);
+int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches);
+
+/* Tuning knobs (not needed for correct results):
+ *   "attention_splits"            0 = choose automatically, 1..16 = key-range splits
+ *   "attention_target_workgroups" workgroups the automatic choice aims for (default 512) */
+int kv_set_option(kv_handle* h, const char* name, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVX_H */

@@ -1,0 +1,524 @@
+// Host side of libkvx: configuration checks, the one-time device arena, per-cache
+// bookkeeping (lengths are a function of the frame count, so the host never reads
+// anything back during a step) and the launch sequence of a step.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/kvx.h"
+#include "kvx_dev.h"
+
+using namespace kvx;
+
+namespace {
+
+struct CacheState {
+  int32_t frames = 0;
+  int32_t t_c = 0;
+  int32_t cur = 0;
+  int32_t last_pruned = 0;
+  int32_t last_scores_len = 0;
+  int64_t dropped = 0;
+};
+
+struct TimedLaunch {
+  hipEvent_t start, stop;
+  int kernel;
+};
+
+thread_local std::string g_init_error;
+
+int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+struct kv_handle {
+  kv_config cfg{};
+  Geometry geo{};
+  std::vector<CacheState> caches;
+  uint8_t* arena = nullptr;
+  uint8_t* scratch = nullptr;
+  float* part_o = nullptr;
+  float* part_ml = nullptr;
+  int64_t bytes_arena = 0, bytes_scratch = 0, bytes_part = 0;
+  int32_t slots_cap = 0;
+  int32_t splits_override = 0;
+  int32_t target_wgs = 512;
+  int device = 0;
+  std::string err;
+  // timing
+  uint32_t timing_mask = 0;
+  std::vector<TimedLaunch> timed;
+  std::vector<TimedLaunch> free_events;
+};
+
+namespace {
+
+int fail(kv_handle* h, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (h) h->err = buf; else g_init_error = buf;
+  return code;
+}
+
+bool is_bits(int b) { return b == 2 || b == 4 || b == 8; }
+
+int validate(const kv_config* c) {
+  if (!c) return fail(nullptr, KV_E_INVAL, "kv_init: cfg is NULL");
+  if (c->n_streams < 1 || c->n_layers < 1) return fail(nullptr, KV_E_INVAL, "kv_init: n_streams and n_layers must be >= 1");
+  if ((int64_t)c->n_streams * c->n_layers > (1 << 20)) return fail(nullptr, KV_E_RANGE, "kv_init: too many caches");
+  if (c->n_heads < 1 || c->n_heads > 64) return fail(nullptr, KV_E_INVAL, "kv_init: n_heads must be in [1, 64]");
+  if (c->head_dim != kHeadDim) return fail(nullptr, KV_E_INVAL, "kv_init: head_dim must be 64");
+  if (c->tokens_per_frame < 1 || c->tokens_per_frame > (1 << 20)) return fail(nullptr, KV_E_INVAL, "kv_init: tokens_per_frame out of range");
+  if (c->n_special < 0 || c->n_special > c->tokens_per_frame) return fail(nullptr, KV_E_INVAL, "kv_init: n_special must be in [0, tokens_per_frame]");
+  if (c->pool_group < 1) return fail(nullptr, KV_E_INVAL, "kv_init: pool_group must be >= 1");
+  if (c->in_dtype != KV_BF16 && c->in_dtype != KV_F32) return fail(nullptr, KV_E_INVAL, "kv_init: in_dtype must be KV_BF16 or KV_F32");
+  if (c->out_dtype != KV_BF16 && c->out_dtype != KV_F32) return fail(nullptr, KV_E_INVAL, "kv_init: out_dtype must be KV_BF16 or KV_F32");
+  if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return fail(nullptr, KV_E_INVAL, "kv_init: softmax_scale must be finite and >= 0");
+  if (c->mode == KV_COMPRESSED) {
+    if ((int64_t)c->budget_tokens < 2 * (int64_t)c->tokens_per_frame)
+      return fail(nullptr, KV_E_INVAL, "kv_init: budget_tokens must be >= 2 * tokens_per_frame (first and current frame are always kept)");
+    if (c->budget_tokens > (1 << 22)) return fail(nullptr, KV_E_RANGE, "kv_init: budget_tokens too large");
+    if (!is_bits(c->k_bits) || !is_bits(c->v_bits)) return fail(nullptr, KV_E_INVAL, "kv_init: k_bits and v_bits must be 2, 4 or 8");
+    if (c->k_group != 32 && c->k_group != 64) return fail(nullptr, KV_E_INVAL, "kv_init: k_group must be 32 or 64");
+    if (c->v_group != 32 && c->v_group != 64) return fail(nullptr, KV_E_INVAL, "kv_init: v_group must be 32 or 64");
+  } else if (c->mode == KV_UNCOMPRESSED_BF16) {
+    if (c->max_frames < 1) return fail(nullptr, KV_E_INVAL, "kv_init: max_frames must be >= 1 in KV_UNCOMPRESSED_BF16 mode");
+    if ((int64_t)c->max_frames * c->tokens_per_frame > (1ll << 28)) return fail(nullptr, KV_E_RANGE, "kv_init: max_frames * tokens_per_frame too large");
+  } else {
+    return fail(nullptr, KV_E_INVAL, "kv_init: unknown mode");
+  }
+  return KV_OK;
+}
+
+int pick_splits(const kv_handle* h, int n_items, int min_tiles) {
+  const Geometry& g = h->geo;
+  int s;
+  if (h->splits_override > 0) {
+    s = h->splits_override;
+  } else {
+    const int base = n_items * g.H * (g.n_pad / kQTile);
+    s = (h->target_wgs + base / 2) / base;
+  }
+  s = std::max(1, std::min(s, (int)kMaxSplits));
+  s = std::min(s, std::max(1, min_tiles));
+  return s;
+}
+
+void record(kv_handle* h, int kernel, bool start, hipStream_t st) {
+  if (!(h->timing_mask & (1u << kernel))) return;
+  if (start) {
+    TimedLaunch t;
+    if (!h->free_events.empty()) {
+      t = h->free_events.back();
+      h->free_events.pop_back();
+    } else {
+      if (h->timed.size() >= 16384) return;
+      if (hipEventCreate(&t.start) != hipSuccess) return;
+      if (hipEventCreate(&t.stop) != hipSuccess) { hipEventDestroy(t.start); return; }
+    }
+    t.kernel = kernel;
+    hipEventRecord(t.start, st);
+    h->timed.push_back(t);
+  } else {
+    if (h->timed.empty() || h->timed.back().kernel != kernel) return;
+    hipEventRecord(h->timed.back().stop, st);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int kv_init(const kv_config* cfg, kv_handle** out) {
+  if (!out) return fail(nullptr, KV_E_INVAL, "kv_init: out is NULL");
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc != KV_OK) return rc;
+  kv_handle* h = new (std::nothrow) kv_handle();
+  if (!h) return fail(nullptr, KV_E_NOMEM, "kv_init: host allocation failed");
+  h->cfg = *cfg;
+  const kv_config& c = h->cfg;
+  Geometry& g = h->geo;
+  const bool unc = c.mode == KV_UNCOMPRESSED_BF16;
+  g.H = c.n_heads;
+  g.n = c.tokens_per_frame;
+  g.n_special = c.n_special;
+  g.pool_group = c.pool_group;
+  g.n_pooled = c.n_special + (c.tokens_per_frame - c.n_special + c.pool_group - 1) / c.pool_group;
+  g.budget = unc ? c.max_frames * c.tokens_per_frame : c.budget_tokens;
+  g.t_cap = (int32_t)align_up(g.budget, 64);
+  g.k_bits = unc ? 16 : c.k_bits;
+  g.v_bits = unc ? 16 : c.v_bits;
+  g.k_group = unc ? 64 : c.k_group;
+  g.v_group = unc ? 64 : c.v_group;
+  g.g_cap = g.t_cap / g.k_group;
+  g.in_f32 = c.in_dtype == KV_F32;
+  g.out_f32 = c.out_dtype == KV_F32;
+  g.uncompressed = unc;
+  g.n_pad = (int32_t)align_up(g.n, kQTile);
+  const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / std::sqrt((float)kHeadDim);
+  g.scale_log2 = scale * 1.4426950408889634f;
+
+  // one half of a cache
+  CacheLayout& L = g.lay;
+  int64_t off = 0;
+  const int64_t k_row = (int64_t)kHeadDim * g.k_bits / 8, v_row = (int64_t)kHeadDim * g.v_bits / 8;
+  L.k_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * k_row, 256);
+  L.k_scale = off; off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
+  L.k_zero = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
+  L.v_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * v_row, 256);
+  L.v_meta = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * (int64_t)sizeof(VMeta)), 256);
+  L.ids = off;     off = align_up(off + (int64_t)g.t_cap * 4, 256);
+  L.half_bytes = off;
+  L.cache_bytes = unc ? off : 2 * off;
+
+  ScratchLayout& S = g.sl;
+  off = 0;
+  S.qbar = off;   off = align_up(off + (int64_t)g.n_pooled * kHeadDim * 4, 256);
+  S.qt = off;     off = align_up(off + kHeadDim * 4, 256);
+  S.dots = off;   off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * 4), 256);
+  S.scores = off; off = align_up(off + (unc ? 0 : (int64_t)g.t_cap * 4), 256);
+  S.keys = off;   off = align_up(off + (unc ? 0 : (int64_t)g.t_cap * 4), 256);
+  S.keep = off;   off = align_up(off + (unc ? 0 : (int64_t)g.t_cap * 4), 256);
+  S.sel = off;    off = align_up(off + 64, 256);
+  S.bytes = off;
+
+  const int64_t n_caches = (int64_t)c.n_streams * c.n_layers;
+  h->caches.assign((size_t)n_caches, CacheState());
+  h->slots_cap = 0;
+  for (int items = 1; items <= kMaxItems; ++items) h->slots_cap = std::max(h->slots_cap, items * std::max(pick_splits(h, items, 1 << 30), 1));
+  h->slots_cap = std::max(h->slots_cap, (int32_t)kMaxSplits);
+  h->bytes_arena = n_caches * L.cache_bytes;
+  h->bytes_scratch = n_caches * S.bytes;
+  const int64_t part_o_bytes = (int64_t)h->slots_cap * g.H * g.n_pad * kHeadDim * 4;
+  const int64_t part_ml_bytes = (int64_t)h->slots_cap * g.H * g.n_pad * 2 * 4;
+  h->bytes_part = part_o_bytes + part_ml_bytes;
+
+  if (hipGetDevice(&h->device) != hipSuccess) {
+    rc = fail(nullptr, KV_E_HIP, "kv_init: no HIP device: %s", hipGetErrorString(hipGetLastError()));
+    delete h;
+    return rc;
+  }
+  hipError_t e1 = hipMalloc((void**)&h->arena, (size_t)h->bytes_arena);
+  hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&h->scratch, (size_t)h->bytes_scratch) : e1;
+  hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&h->part_o, (size_t)part_o_bytes) : e2;
+  hipError_t e4 = e3 == hipSuccess ? hipMalloc((void**)&h->part_ml, (size_t)part_ml_bytes) : e3;
+  if (e4 != hipSuccess) {
+    rc = fail(nullptr, e4 == hipErrorOutOfMemory ? KV_E_NOMEM : KV_E_HIP, "kv_init: device allocation of %lld bytes failed: %s",
+              (long long)(h->bytes_arena + h->bytes_scratch + h->bytes_part), hipGetErrorString(e4));
+    (void)hipGetLastError();
+    kv_destroy(h);
+    return rc;
+  }
+  if (hipMemset(h->arena, 0, (size_t)h->bytes_arena) != hipSuccess || hipMemset(h->scratch, 0, (size_t)h->bytes_scratch) != hipSuccess ||
+      hipDeviceSynchronize() != hipSuccess) {
+    rc = fail(nullptr, KV_E_HIP, "kv_init: clearing the arena failed: %s", hipGetErrorString(hipGetLastError()));
+    kv_destroy(h);
+    return rc;
+  }
+  g.arena = h->arena;
+  g.scratch = h->scratch;
+  g.part_o = h->part_o;
+  g.part_ml = h->part_ml;
+  *out = h;
+  return KV_OK;
+}
+
+int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride, int64_t head_stride, void* hip_stream) {
+  if (!h) return KV_E_INVAL;
+  if (n_items < 1 || !items) return fail(h, KV_E_INVAL, "kv_step: no items");
+  const kv_config& c = h->cfg;
+  const Geometry& g0 = h->geo;
+  const int64_t elt = g0.in_f32 ? 4 : 2;
+  if (head_stride < kHeadDim || tok_stride < kHeadDim) return fail(h, KV_E_INVAL, "kv_step: strides must be >= head_dim");
+  const int64_t oelt = g0.out_f32 ? 4 : 2;
+  if ((tok_stride * elt) % 16 || (head_stride * elt) % 16 || (tok_stride * oelt) % 16 || (head_stride * oelt) % 16)
+    return fail(h, KV_E_INVAL, "kv_step: strides must keep rows 16-byte aligned");
+  std::vector<char> seen(h->caches.size(), 0);
+  for (int i = 0; i < n_items; ++i) {
+    const kv_step_item& it = items[i];
+    if (it.stream < 0 || it.stream >= c.n_streams || it.layer < 0 || it.layer >= c.n_layers)
+      return fail(h, KV_E_RANGE, "kv_step: item %d: stream %d / layer %d out of range", i, it.stream, it.layer);
+    if (!it.q || !it.k || !it.v || !it.out) return fail(h, KV_E_INVAL, "kv_step: item %d: NULL pointer", i);
+    if (((uintptr_t)it.q | (uintptr_t)it.k | (uintptr_t)it.v | (uintptr_t)it.out) & 15)
+      return fail(h, KV_E_INVAL, "kv_step: item %d: pointers must be 16-byte aligned", i);
+    const size_t ci = (size_t)it.stream * c.n_layers + it.layer;
+    if (seen[ci]) return fail(h, KV_E_INVAL, "kv_step: cache (stream %d, layer %d) appears twice in one batch", it.stream, it.layer);
+    seen[ci] = 1;
+    if (g0.uncompressed && h->caches[ci].frames >= c.max_frames)
+      return fail(h, KV_E_STATE, "kv_step: cache (stream %d, layer %d) already holds max_frames frames", it.stream, it.layer);
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  for (int base = 0; base < n_items; base += kMaxItems) {
+    const int cnt = std::min<int>(kMaxItems, n_items - base);
+    KvxBatch b;
+    b.g = g0;
+    b.g.tok_stride = tok_stride;
+    b.g.head_stride = head_stride;
+    b.g.out_tok_stride = tok_stride;
+    b.g.out_head_stride = head_stride;
+    b.n_items = cnt;
+    b.pad = 0;
+    int max_tc = 0, max_tnew = 0, min_tiles = 1 << 30;
+    bool any_prune = false;
+    for (int i = 0; i < cnt; ++i) {
+      const kv_step_item& src = items[base + i];
+      const size_t ci = (size_t)src.stream * c.n_layers + src.layer;
+      const CacheState& cs = h->caches[ci];
+      Item& it = b.items[i];
+      it.q = src.q; it.k = src.k; it.v = src.v; it.out = src.out;
+      it.cache = (int32_t)ci;
+      it.t_c = cs.t_c;
+      it.cur = cs.cur;
+      it.prune = (!g0.uncompressed && cs.t_c + g0.n > g0.budget) ? 1 : 0;
+      it.frame = cs.frames;
+      it.g0_host = cs.t_c / g0.k_group;
+      it.pad0 = it.pad1 = 0;
+      any_prune |= it.prune != 0;
+      max_tc = std::max(max_tc, cs.t_c);
+      max_tnew = std::max(max_tnew, std::min(cs.t_c + g0.n, g0.budget));
+      const int tiles = (cs.t_c + kTileK - 1) / kTileK + (g0.n + kTileK - 1) / kTileK;
+      min_tiles = std::min(min_tiles, tiles);
+    }
+    b.g.n_splits = pick_splits(h, cnt, min_tiles);
+    if (cnt * b.g.n_splits > h->slots_cap) b.g.n_splits = std::max(1, h->slots_cap / cnt);
+
+    record(h, KV_K_ATTENTION, true, st);
+    launch_attention(b, 0, st);
+    record(h, KV_K_ATTENTION, false, st);
+    record(h, KV_K_COMBINE, true, st);
+    launch_combine(b, st);
+    record(h, KV_K_COMBINE, false, st);
+    if (g0.uncompressed) {
+      record(h, KV_K_REBUILD_V, true, st);
+      launch_append_bf16(b, st);
+      record(h, KV_K_REBUILD_V, false, st);
+    } else {
+      if (any_prune) {
+        record(h, KV_K_POOL, true, st);
+        launch_pool(b, st);
+        record(h, KV_K_POOL, false, st);
+        record(h, KV_K_SCORE, true, st);
+        launch_score(b, max_tc, st);
+        record(h, KV_K_SCORE, false, st);
+        record(h, KV_K_SELECT, true, st);
+        launch_select(b, st);
+        record(h, KV_K_SELECT, false, st);
+      }
+      record(h, KV_K_REBUILD_K, true, st);
+      launch_rebuild_k(b, max_tnew, st);
+      record(h, KV_K_REBUILD_K, false, st);
+      record(h, KV_K_REBUILD_V, true, st);
+      launch_rebuild_v(b, max_tnew, st);
+      record(h, KV_K_REBUILD_V, false, st);
+    }
+    hipError_t le = hipGetLastError();
+    if (le != hipSuccess) return fail(h, KV_E_HIP, "kv_step: launch failed: %s", hipGetErrorString(le));
+
+    for (int i = 0; i < cnt; ++i) {
+      CacheState& cs = h->caches[(size_t)b.items[i].cache];
+      const int t_all = cs.t_c + g0.n;
+      cs.last_pruned = b.items[i].prune;
+      cs.last_scores_len = b.items[i].prune ? cs.t_c - g0.n : 0;
+      if (b.items[i].prune) cs.dropped += t_all - g0.budget;
+      cs.t_c = std::min(t_all, g0.budget);
+      cs.frames += 1;
+      if (!g0.uncompressed) cs.cur ^= 1;
+    }
+  }
+  return KV_OK;
+}
+
+int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v, int64_t tok_stride,
+            int64_t head_stride, void* out, void* hip_stream) {
+  kv_step_item it;
+  it.stream = stream;
+  it.layer = layer;
+  it.q = q;
+  it.k = k;
+  it.v = v;
+  it.out = out;
+  return kv_step_batched(h, 1, &it, tok_stride, head_stride, hip_stream);
+}
+
+int kv_stats(kv_handle* h, kv_stats_t* s) {
+  if (!h) return KV_E_INVAL;
+  if (!s) return fail(h, KV_E_INVAL, "kv_stats: stats is NULL");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(h, KV_E_HIP, "kv_stats: %s", hipGetErrorString(hipGetLastError()));
+  const Geometry& g = h->geo;
+  const int64_t nc = (int64_t)h->caches.size();
+  const int64_t halves = g.uncompressed ? 1 : 2;
+  memset(s, 0, sizeof *s);
+  s->bytes_allocated = h->bytes_arena + h->bytes_scratch + h->bytes_part;
+  s->bytes_k_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.k_bits / 8);
+  s->bytes_k_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.g_cap * kHeadDim * 8);
+  s->bytes_v_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.v_bits / 8);
+  s->bytes_v_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * 8);
+  s->bytes_ids = nc * halves * (int64_t)g.t_cap * 4;
+  s->bytes_scratch = h->bytes_scratch + h->bytes_part;
+  s->n_caches = (int32_t)nc;
+  int32_t mn = INT32_MAX, mx = 0;
+  for (size_t i = 0; i < h->caches.size(); ++i) {
+    const CacheState& cs = h->caches[i];
+    s->frames_seen_total += cs.frames;
+    s->tokens_dropped_total += cs.dropped;
+    mn = std::min(mn, cs.t_c);
+    mx = std::max(mx, cs.t_c);
+    if (!g.uncompressed) {
+      int32_t sel[4];
+      if (hipMemcpy(sel, h->scratch + (int64_t)i * g.sl.bytes + g.sl.sel, sizeof sel, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(h, KV_E_HIP, "kv_stats: %s", hipGetErrorString(hipGetLastError()));
+      s->k_groups_rebuilt_total += sel[2];
+    }
+  }
+  s->cache_len_min = mn;
+  s->cache_len_max = mx;
+  const int64_t T = mx;
+  if (g.uncompressed) {
+    s->bytes_live_per_cache = 2 * (int64_t)g.H * T * kHeadDim * 2;
+  } else {
+    const int64_t groups = (T + g.k_group - 1) / g.k_group;
+    s->bytes_live_per_cache = (int64_t)g.H * T * kHeadDim * g.k_bits / 8 + (int64_t)g.H * groups * kHeadDim * 8 +
+                              (int64_t)g.H * T * kHeadDim * g.v_bits / 8 + (int64_t)g.H * T * (kHeadDim / g.v_group) * 8 + T * 4;
+  }
+  return KV_OK;
+}
+
+int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* x) {
+  if (!h) return KV_E_INVAL;
+  if (!x) return fail(h, KV_E_INVAL, "kv_export: bufs is NULL");
+  const kv_config& c = h->cfg;
+  if (stream < 0 || stream >= c.n_streams || layer < 0 || layer >= c.n_layers) return fail(h, KV_E_RANGE, "kv_export: stream/layer out of range");
+  const Geometry& g = h->geo;
+  if (g.uncompressed) return fail(h, KV_E_STATE, "kv_export: not available in KV_UNCOMPRESSED_BF16 mode");
+  const size_t ci = (size_t)stream * c.n_layers + layer;
+  const CacheState& cs = h->caches[ci];
+  const int T = cs.t_c;
+  if (x->capacity_tokens < T) return fail(h, KV_E_RANGE, "kv_export: capacity_tokens %d < cache length %d", x->capacity_tokens, T);
+  if (hipDeviceSynchronize() != hipSuccess) return fail(h, KV_E_HIP, "kv_export: %s", hipGetErrorString(hipGetLastError()));
+  x->cache_len = T;
+  x->frames_seen = cs.frames;
+  x->last_keep_len = cs.last_pruned ? g.budget : 0;
+  x->last_scores_len = cs.last_scores_len;
+  const uint8_t* half = h->arena + (int64_t)ci * g.lay.cache_bytes + (int64_t)cs.cur * g.lay.half_bytes;
+  const uint8_t* sc = h->scratch + (int64_t)ci * g.sl.bytes;
+  const int H = g.H;
+  const int G = (T + g.k_group - 1) / g.k_group;
+  const int ngv = kHeadDim / g.v_group;
+  auto d2h = [&](void* dst, const void* src, size_t bytes) { return bytes == 0 || hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost) == hipSuccess; };
+  bool ok = true;
+  if (x->ids) ok &= d2h(x->ids, half + g.lay.ids, (size_t)T * 4);
+  auto unpack = [&](uint8_t* dst, int64_t lay_off, int bits) {
+    const int row = kHeadDim * bits / 8;
+    std::vector<uint8_t> tmp((size_t)T * row);
+    for (int hh = 0; hh < H && ok; ++hh) {
+      ok &= d2h(tmp.data(), half + lay_off + (int64_t)hh * g.t_cap * row, tmp.size());
+      for (int j = 0; j < T; ++j)
+        for (int ch = 0; ch < kHeadDim; ++ch) {
+          const int bit = ch * bits;
+          dst[((int64_t)hh * T + j) * kHeadDim + ch] = (uint8_t)((tmp[(size_t)j * row + (bit >> 3)] >> (bit & 7)) & ((1 << bits) - 1));
+        }
+    }
+  };
+  if (x->k_codes) unpack(x->k_codes, g.lay.k_codes, g.k_bits);
+  if (x->v_codes) unpack(x->v_codes, g.lay.v_codes, g.v_bits);
+  for (int hh = 0; hh < H && ok; ++hh) {
+    if (x->k_scale) ok &= d2h(x->k_scale + (int64_t)hh * G * kHeadDim, half + g.lay.k_scale + (int64_t)hh * g.g_cap * kHeadDim * 4, (size_t)G * kHeadDim * 4);
+    if (x->k_zero) ok &= d2h(x->k_zero + (int64_t)hh * G * kHeadDim, half + g.lay.k_zero + (int64_t)hh * g.g_cap * kHeadDim * 4, (size_t)G * kHeadDim * 4);
+  }
+  if (x->v_scale || x->v_zero) {
+    std::vector<VMeta> tmp((size_t)T * ngv);
+    for (int hh = 0; hh < H && ok; ++hh) {
+      ok &= d2h(tmp.data(), half + g.lay.v_meta + (int64_t)hh * g.t_cap * ngv * sizeof(VMeta), tmp.size() * sizeof(VMeta));
+      for (size_t i = 0; i < tmp.size(); ++i) {
+        if (x->v_scale) x->v_scale[(size_t)hh * T * ngv + i] = tmp[i].s;
+        if (x->v_zero) x->v_zero[(size_t)hh * T * ngv + i] = tmp[i].z;
+      }
+    }
+  }
+  if (cs.last_pruned) {
+    if (x->last_keep) ok &= d2h(x->last_keep, sc + g.sl.keep, (size_t)g.budget * 4);
+    if (x->last_scores) ok &= d2h(x->last_scores, sc + g.sl.scores, (size_t)cs.last_scores_len * 4);
+  }
+  if (!ok) return fail(h, KV_E_HIP, "kv_export: copy failed: %s", hipGetErrorString(hipGetLastError()));
+  return KV_OK;
+}
+
+int kv_reset(kv_handle* h, int32_t stream, int32_t layer) {
+  if (!h) return KV_E_INVAL;
+  const kv_config& c = h->cfg;
+  if (stream == -1 && layer == -1) {
+    for (auto& cs : h->caches) cs = CacheState();
+    return KV_OK;
+  }
+  if (stream < 0 || stream >= c.n_streams || layer < 0 || layer >= c.n_layers) return fail(h, KV_E_RANGE, "kv_reset: stream/layer out of range");
+  h->caches[(size_t)stream * c.n_layers + layer] = CacheState();
+  return KV_OK;
+}
+
+void kv_destroy(kv_handle* h) {
+  if (!h) return;
+  for (auto& t : h->timed) { hipEventDestroy(t.start); hipEventDestroy(t.stop); }
+  for (auto& t : h->free_events) { hipEventDestroy(t.start); hipEventDestroy(t.stop); }
+  if (h->arena) hipFree(h->arena);
+  if (h->scratch) hipFree(h->scratch);
+  if (h->part_o) hipFree(h->part_o);
+  if (h->part_ml) hipFree(h->part_ml);
+  delete h;
+}
+
+const char* kv_last_error(kv_handle* h) { return h ? h->err.c_str() : g_init_error.c_str(); }
+
+int kv_set_timing(kv_handle* h, uint32_t kernel_mask) {
+  if (!h) return KV_E_INVAL;
+  h->timing_mask = kernel_mask;
+  return KV_OK;
+}
+
+int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches) {
+  if (!h) return KV_E_INVAL;
+  if (!total_ms || !launches) return fail(h, KV_E_INVAL, "kv_read_timing: NULL output");
+  for (int i = 0; i < KV_K_COUNT; ++i) { total_ms[i] = 0.f; launches[i] = 0; }
+  for (auto& t : h->timed) {
+    float ms = 0.f;
+    if (hipEventSynchronize(t.stop) == hipSuccess && hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+      total_ms[t.kernel] += ms;
+      launches[t.kernel] += 1;
+    } else {
+      (void)hipGetLastError();
+    }
+    h->free_events.push_back(t);
+  }
+  h->timed.clear();
+  return KV_OK;
+}
+
+int kv_set_option(kv_handle* h, const char* name, int64_t value) {
+  if (!h) return KV_E_INVAL;
+  if (!name) return fail(h, KV_E_INVAL, "kv_set_option: name is NULL");
+  if (!strcmp(name, "attention_splits")) {
+    if (value < 0 || value > kMaxSplits) return fail(h, KV_E_RANGE, "kv_set_option: attention_splits must be in [0, %d]", (int)kMaxSplits);
+    h->splits_override = (int32_t)value;
+    return KV_OK;
+  }
+  if (!strcmp(name, "attention_target_workgroups")) {
+    if (value < 1 || value > 65536) return fail(h, KV_E_RANGE, "kv_set_option: attention_target_workgroups out of range");
+    h->target_wgs = (int32_t)value;
+    return KV_OK;
+  }
+  return fail(h, KV_E_INVAL, "kv_set_option: unknown option '%s'", name);
+}
+
+}  // extern "C"

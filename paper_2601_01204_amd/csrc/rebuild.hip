@@ -1,0 +1,349 @@
+// Building the next cache from the kept tokens and the new frame (paper Sec. 3.2 keep
+// set, Sec. 3.3 Eq. 7-9): stable compaction along the keep list, per-channel key groups
+// re-quantised where their ordered membership changed, value codes carried, the new
+// frame's values quantised per token.
+//
+// Everything here decides integers that are compared bit-for-bit, so the arithmetic is
+// fp32 with one rounding per operation: s = (max - min) / (2^b - 1) with an IEEE divide,
+// z = rint(-min / s), code = clamp(int(rint(x / s)) + z, 0, 2^b - 1), rint to nearest
+// even.  A constant group takes s = |min| (1 when min is 0).
+#include "kvx_dev.h"
+
+namespace kvx {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+
+__device__ __forceinline__ void quant_params(float mn, float mx, int levels, float& s, int32_t& z) {
+  s = (mx - mn) / (float)levels;
+  if (mx == mn) s = (mn != 0.f) ? fabsf(mn) : 1.0f;
+  z = (int32_t)rintf((-mn) / s);
+}
+
+__device__ __forceinline__ int quant_code(float x, float s, int32_t z, int levels) {
+  const int q = (int)rintf(x / s) + z;
+  return min(max(q, 0), levels);
+}
+
+// 16 consecutive channels of one row as fp32, from a quantised row (with that row's group
+// metadata) or from an input row.
+template <int B>
+__device__ __forceinline__ void unpack16(const uint8_t* p, uint32_t (&w)[4]) {
+  if constexpr (B == 2) {
+    w[0] = *reinterpret_cast<const uint32_t*>(p);
+  } else if constexpr (B == 4) {
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    w[0] = t.x; w[1] = t.y;
+  } else {
+    const uint4 t = *reinterpret_cast<const uint4*>(p);
+    w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+  }
+}
+template <int B>
+__device__ __forceinline__ int code16(const uint32_t (&w)[4], int e) {
+  if constexpr (B == 2) return (int)((w[0] >> (2 * e)) & 3u);
+  if constexpr (B == 4) return (int)((w[e >> 3] >> (4 * (e & 7))) & 0xFu);
+  return (int)((w[e >> 2] >> (8 * (e & 3))) & 0xFFu);
+}
+template <int B>
+__device__ __forceinline__ void pack16(const int (&code)[16], uint8_t* p) {
+  if constexpr (B == 2) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) w |= (uint32_t)code[e] << (2 * e);
+    *reinterpret_cast<uint32_t*>(p) = w;
+  } else if constexpr (B == 4) {
+    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      w0 |= (uint32_t)code[e] << (4 * e);
+      w1 |= (uint32_t)code[8 + e] << (4 * e);
+    }
+    *reinterpret_cast<uint2*>(p) = make_uint2(w0, w1);
+  } else {
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < 16; ++e) w[e >> 2] |= (uint32_t)code[e] << (8 * (e & 3));
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+__device__ __forceinline__ void load_input16(const void* base, int64_t off, int in_f32, float (&x)[16]) {
+  if (in_f32) {
+    const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + off);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 t = p[i];
+      x[4 * i] = t.x; x[4 * i + 1] = t.y; x[4 * i + 2] = t.z; x[4 * i + 3] = t.w;
+    }
+  } else {
+    const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + off);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint4 t = p[i];
+      const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        x[8 * i + 2 * k] = __uint_as_float(w[k] << 16);
+        x[8 * i + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+      }
+    }
+  }
+}
+
+// Keys.  One block = 64 consecutive positions of the next cache for one head (one key
+// group of 64, or two of 32).  A group wholly below the first dropped position has the
+// same ordered members as before and is copied verbatim; every other group is rebuilt
+// from the fp32 values of its members: de-quantised codes for surviving tokens, input
+// values for the new frame.
+template <int B>
+__global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
+  const Geometry& g = b.g;
+  const Item& it = b.items[blockIdx.z];
+  const int h = blockIdx.y;
+  const int t_c = it.t_c;
+  const int t_new = min(t_c + g.n, g.budget);
+  const int p0 = blockIdx.x * kTileK;
+  if (p0 >= t_new) return;
+  const uint8_t* cur = cache_half(g, it.cache, it.cur);
+  uint8_t* nxt = cache_half(g, it.cache, it.cur ^ 1);
+  uint8_t* sc = cache_scratch(g, it.cache);
+  const int32_t* keep = reinterpret_cast<const int32_t*>(sc + g.sl.keep);
+  int32_t* sel = reinterpret_cast<int32_t*>(sc + g.sl.sel);
+  const int g0 = it.prune ? sel[1] : it.g0_host;      // first group whose membership changed
+  constexpr int kRow = 8 * B;                          // bytes per key row
+  const int levels = (1 << B) - 1;
+
+  const int tid = threadIdx.x;
+  const int r = tid >> 2, cb = tid & 3;                // row in block, 16-channel block
+  const int p = p0 + r;
+  const bool active = p < t_new;
+  const int grp = p / g.k_group;
+  const bool carried = grp < g0;
+
+  __shared__ float vals[kTileK][kHeadDim + 1];
+  __shared__ float pmin[4][kHeadDim], pmax[4][kHeadDim];
+  __shared__ float gs[2][kHeadDim];
+  __shared__ int32_t gz[2][kHeadDim];
+
+  float x[16];
+  uint32_t wsrc[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int e = 0; e < 16; ++e) x[e] = 0.f;
+  if (active) {
+    const int src = it.prune ? keep[p] : p;
+    if (src < t_c) {
+      unpack16<B>(cur + g.lay.k_codes + ((int64_t)h * g.t_cap + src) * kRow + cb * 2 * B, wsrc);
+      if (!carried) {
+        const int sg = src / g.k_group;
+        const int64_t moff = ((int64_t)h * g.g_cap + sg) * kHeadDim + cb * 16;
+        const float* sp = reinterpret_cast<const float*>(cur + g.lay.k_scale) + moff;
+        const int32_t* zp = reinterpret_cast<const int32_t*>(cur + g.lay.k_zero) + moff;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) x[e] = sp[e] * (float)(code16<B>(wsrc, e) - zp[e]);
+      }
+    } else {
+      load_input16(it.k, (int64_t)(src - t_c) * g.tok_stride + (int64_t)h * g.head_stride + cb * 16, g.in_f32, x);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) vals[r][cb * 16 + e] = x[e];
+  __syncthreads();
+
+  // per-channel min / max over each quarter of the rows
+  {
+    const int c = tid & 63, qtr = tid >> 6;
+    float mn = INFINITY, mx = -INFINITY;
+    for (int rr = qtr * 16; rr < qtr * 16 + 16; ++rr) {
+      if (p0 + rr < t_new) {
+        const float v = vals[rr][c];
+        mn = fminf(mn, v);
+        mx = fmaxf(mx, v);
+      }
+    }
+    pmin[qtr][c] = mn;
+    pmax[qtr][c] = mx;
+  }
+  __syncthreads();
+
+  const int groups_in_block = kTileK / g.k_group;      // 1 or 2
+  if (tid < groups_in_block * 64) {
+    const int gi = tid >> 6, c = tid & 63;
+    const int ggrp = p0 / g.k_group + gi;
+    const int first_row = gi * g.k_group;
+    if (p0 + first_row < t_new) {
+      const int64_t moff = ((int64_t)h * g.g_cap + ggrp) * kHeadDim + c;
+      float s;
+      int32_t z;
+      if (ggrp < g0) {
+        s = reinterpret_cast<const float*>(cur + g.lay.k_scale)[moff];
+        z = reinterpret_cast<const int32_t*>(cur + g.lay.k_zero)[moff];
+      } else {
+        const int q_lo = first_row / 16, q_hi = (first_row + g.k_group) / 16;
+        float mn = INFINITY, mx = -INFINITY;
+        for (int qq = q_lo; qq < q_hi; ++qq) {
+          mn = fminf(mn, pmin[qq][c]);
+          mx = fmaxf(mx, pmax[qq][c]);
+        }
+        quant_params(mn, mx, levels, s, z);
+        if (h == 0 && c == 0) atomicAdd(&sel[2], 1);
+      }
+      gs[gi][c] = s;
+      gz[gi][c] = z;
+      reinterpret_cast<float*>(nxt + g.lay.k_scale)[moff] = s;
+      reinterpret_cast<int32_t*>(nxt + g.lay.k_zero)[moff] = z;
+    }
+  }
+  __syncthreads();
+
+  if (active) {
+    uint8_t* dst = nxt + g.lay.k_codes + ((int64_t)h * g.t_cap + p) * kRow + cb * 2 * B;
+    if (carried) {
+      if constexpr (B == 2) *reinterpret_cast<uint32_t*>(dst) = wsrc[0];
+      else if constexpr (B == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(wsrc[0], wsrc[1]);
+      else *reinterpret_cast<uint4*>(dst) = make_uint4(wsrc[0], wsrc[1], wsrc[2], wsrc[3]);
+    } else {
+      const int gi = r / g.k_group;
+      int code[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) code[e] = quant_code(x[e], gs[gi][cb * 16 + e], gz[gi][cb * 16 + e], levels);
+      pack16<B>(code, dst);
+    }
+  }
+}
+
+// Values and token ids.  One block = 64 consecutive positions of the next cache for one
+// head.  Surviving tokens carry their codes and (s, z); tokens of the new frame are
+// quantised per token over groups of v_group channels.
+template <int B>
+__global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b) {
+  const Geometry& g = b.g;
+  const Item& it = b.items[blockIdx.z];
+  const int h = blockIdx.y;
+  const int t_c = it.t_c;
+  const int t_new = min(t_c + g.n, g.budget);
+  const int tid = threadIdx.x;
+  const int r = tid >> 2, cb = tid & 3;
+  const int p = blockIdx.x * kTileK + r;
+  const bool active = p < t_new;           // uniform over each group of 4 lanes
+  const uint8_t* cur = cache_half(g, it.cache, it.cur);
+  uint8_t* nxt = cache_half(g, it.cache, it.cur ^ 1);
+  const int32_t* keep = reinterpret_cast<const int32_t*>(cache_scratch(g, it.cache) + g.sl.keep);
+  constexpr int kRow = 8 * B;
+  const int levels = (1 << B) - 1;
+  const int ngv = kHeadDim / g.v_group;    // 1 or 2
+  const int lanes_per_group = 4 / ngv;     // 4 or 2 lanes share one value group
+  const int gv = cb / lanes_per_group;
+
+  int src = 0;
+  if (active) src = it.prune ? keep[p] : p;
+  const bool is_new = active && src >= t_c;
+  float x[16];
+  float mn = INFINITY, mx = -INFINITY;
+  if (is_new) {
+    load_input16(it.v, (int64_t)(src - t_c) * g.tok_stride + (int64_t)h * g.head_stride + cb * 16, g.in_f32, x);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      mn = fminf(mn, x[e]);
+      mx = fmaxf(mx, x[e]);
+    }
+  }
+  // min / max over the lanes that share the group (executed by all lanes: no divergence around shuffles)
+  mn = fminf(mn, __shfl_xor(mn, 1));
+  mx = fmaxf(mx, __shfl_xor(mx, 1));
+  if (lanes_per_group == 4) {
+    mn = fminf(mn, __shfl_xor(mn, 2));
+    mx = fmaxf(mx, __shfl_xor(mx, 2));
+  }
+  if (!active) return;
+  uint8_t* dst = nxt + g.lay.v_codes + ((int64_t)h * g.t_cap + p) * kRow + cb * 2 * B;
+  VMeta* mdst = reinterpret_cast<VMeta*>(nxt + g.lay.v_meta) + ((int64_t)h * g.t_cap + p) * ngv + gv;
+  if (is_new) {
+    float s;
+    int32_t z;
+    quant_params(mn, mx, levels, s, z);
+    int code[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) code[e] = quant_code(x[e], s, z, levels);
+    pack16<B>(code, dst);
+    if ((cb % lanes_per_group) == 0) {
+      VMeta m;
+      m.s = s;
+      m.z = z;
+      *mdst = m;
+    }
+  } else {
+    uint32_t w[4] = {0, 0, 0, 0};
+    unpack16<B>(cur + g.lay.v_codes + ((int64_t)h * g.t_cap + src) * kRow + cb * 2 * B, w);
+    if constexpr (B == 2) *reinterpret_cast<uint32_t*>(dst) = w[0];
+    else if constexpr (B == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+    else *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    if ((cb % lanes_per_group) == 0)
+      *mdst = (reinterpret_cast<const VMeta*>(cur + g.lay.v_meta))[((int64_t)h * g.t_cap + src) * ngv + gv];
+  }
+  if (h == 0 && cb == 0) {
+    const int32_t* ids = reinterpret_cast<const int32_t*>(cur + g.lay.ids);
+    int32_t* ids_n = reinterpret_cast<int32_t*>(nxt + g.lay.ids);
+    ids_n[p] = (src < t_c) ? ids[src] : it.frame * g.n + (src - t_c);
+  }
+}
+
+// Uncompressed baseline: append the frame's K and V as bf16 rows [H][t_cap][64].
+__global__ __launch_bounds__(256) void append_bf16_kernel(const KvxBatch b) {
+  const Geometry& g = b.g;
+  const Item& it = b.items[blockIdx.z];
+  const int h = blockIdx.y;
+  const int i = blockIdx.x * 32 + (threadIdx.x >> 3);
+  const int c8 = (threadIdx.x & 7) * 8;
+  if (i >= g.n) return;
+  uint8_t* base = cache_half(g, it.cache, 0);
+  const int64_t off = (int64_t)i * g.tok_stride + (int64_t)h * g.head_stride + c8;
+  const int64_t dsto = ((int64_t)h * g.t_cap + it.t_c + i) * kHeadDim + c8;
+  uint4 kk, vv;
+  if (g.in_f32) {
+    // fp32 input is rounded to bf16 (nearest even) for the baseline cache
+    const float* kp = reinterpret_cast<const float*>(it.k) + off;
+    const float* vp = reinterpret_cast<const float*>(it.v) + off;
+    uint32_t kw[4], vw[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      typedef float f2 __attribute__((ext_vector_type(2)));
+      typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+      f2 a = {kp[2 * e], kp[2 * e + 1]}, c = {vp[2 * e], vp[2 * e + 1]};
+      kw[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, b2));
+      vw[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(c, b2));
+    }
+    kk = make_uint4(kw[0], kw[1], kw[2], kw[3]);
+    vv = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+  } else {
+    kk = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.k) + off);
+    vv = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.v) + off);
+  }
+  *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(base + g.lay.k_codes) + dsto) = kk;
+  *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(base + g.lay.v_codes) + dsto) = vv;
+  if (h == 0 && c8 == 0) reinterpret_cast<int32_t*>(base + g.lay.ids)[it.t_c + i] = it.frame * g.n + i;
+}
+
+void launch_rebuild_k(const KvxBatch& b, int max_tnew, hipStream_t st) {
+  dim3 grid((max_tnew + kTileK - 1) / kTileK, b.g.H, b.n_items);
+  switch (b.g.k_bits) {
+    case 2: hipLaunchKernelGGL(rebuild_k_kernel<2>, grid, dim3(256), 0, st, b); break;
+    case 4: hipLaunchKernelGGL(rebuild_k_kernel<4>, grid, dim3(256), 0, st, b); break;
+    default: hipLaunchKernelGGL(rebuild_k_kernel<8>, grid, dim3(256), 0, st, b); break;
+  }
+}
+
+void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st) {
+  dim3 grid((max_tnew + kTileK - 1) / kTileK, b.g.H, b.n_items);
+  switch (b.g.v_bits) {
+    case 2: hipLaunchKernelGGL(rebuild_v_kernel<2>, grid, dim3(256), 0, st, b); break;
+    case 4: hipLaunchKernelGGL(rebuild_v_kernel<4>, grid, dim3(256), 0, st, b); break;
+    default: hipLaunchKernelGGL(rebuild_v_kernel<8>, grid, dim3(256), 0, st, b); break;
+  }
+}
+
+void launch_append_bf16(const KvxBatch& b, hipStream_t st) {
+  dim3 grid((b.g.n + 31) / 32, b.g.H, b.n_items);
+  hipLaunchKernelGGL(append_bf16_kernel, grid, dim3(256), 0, st, b);
+}
+
+}  // namespace kvx

@@ -1,0 +1,163 @@
+// Top-k selection and keep list (paper Sec. 3.2): keep the first frame, the k best
+// middle tokens (k = L_max - T_first - T_current) and the current frame, in ascending
+// position order.  Integer work throughout: scores are compared through an
+// order-preserving uint32 image of their fp32 bits, equal scores keep the lower
+// position, so the result is unique and bit-exact.
+//
+// One workgroup of 1024 threads per cache: a 4-pass most-significant-byte-first radix
+// select finds the key of the last token to drop, two block scans resolve ties by
+// position and compact the survivors.
+#include "kvx_dev.h"
+
+namespace kvx {
+
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum of one int per thread over a 1024-thread block.
+__device__ __forceinline__ int block_scan_excl(int v, int* wave_sums, int& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  __syncthreads();                 // wave_sums may still be read from a previous call
+  if (lane == 63) wave_sums[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int s = wave_sums[w];
+    if (w < wave) base += s;
+    tot += s;
+  }
+  total = tot;
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
+  const Geometry& g = b.g;
+  const Item& it = b.items[blockIdx.x];
+  if (!it.prune) return;
+  const int n = g.n, t_c = it.t_c, H = g.H;
+  const int M = t_c - n;                 // middle tokens: cache positions n .. t_c - 1
+  const int T = t_c + n;
+  const int n_drop = T - g.budget;       // >= 1
+  const int k_keep = M - n_drop;         // = budget - 2n
+  uint8_t* sc = cache_scratch(g, it.cache);
+  const float* dots = reinterpret_cast<const float*>(sc + g.sl.dots);
+  float* scores = reinterpret_cast<float*>(sc + g.sl.scores);
+  uint32_t* keys = reinterpret_cast<uint32_t*>(sc + g.sl.keys);
+  int32_t* keep = reinterpret_cast<int32_t*>(sc + g.sl.keep);
+  int32_t* sel = reinterpret_cast<int32_t*>(sc + g.sl.sel);
+  const int tid = threadIdx.x;
+
+  __shared__ int hist[256];
+  __shared__ int wave_sums[16];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_remaining;
+  __shared__ int sh_p0;
+
+  // S_j = (D[0,j] + D[1,j] + ... + D[H-1,j]) / H, heads added in order (Eq. 4-6).
+  for (int i = tid; i < M; i += 1024) {
+    float acc = dots[n + i];
+    for (int h = 1; h < H; ++h) acc = acc + dots[(int64_t)h * g.t_cap + n + i];
+    const float s = acc / (float)H;
+    scores[i] = s;
+    keys[i] = order_key(s);
+  }
+  if (tid == 0) {
+    sh_prefix = 0u;
+    sh_remaining = n_drop;
+    sh_p0 = T;
+  }
+  __syncthreads();
+
+  // Key of the n_drop-th smallest element.
+  uint32_t mask = 0u;
+  for (int pass = 3; pass >= 0; --pass) {
+    const int shift = 8 * pass;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = sh_prefix;
+    for (int i = tid; i < M; i += 1024) {
+      const uint32_t key = keys[i];
+      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int rem = sh_remaining, bin = 0;
+      while (bin < 255 && hist[bin] < rem) {
+        rem -= hist[bin];
+        ++bin;
+      }
+      sh_remaining = rem;
+      sh_prefix = prefix | ((uint32_t)bin << shift);
+      if (pass == 0) hist[0] = hist[bin];        // number of keys equal to the threshold
+    }
+    mask |= 0xFFu << shift;
+    __syncthreads();
+  }
+  const uint32_t thr = sh_prefix;
+  const int need_eq = sh_remaining;              // equal-keyed tokens to drop (highest positions first)
+  const int total_eq = hist[0];
+  const int eq_keep = total_eq - need_eq;        // equal-keyed tokens kept: the eq_keep lowest positions
+  __syncthreads();
+
+  // Contiguous chunk of middle positions per thread, so prefix sums follow position order.
+  const int chunk = (M + 1023) / 1024;
+  const int c0 = min(tid * chunk, M), c1 = min(c0 + chunk, M);
+  int eq_cnt = 0;
+  for (int i = c0; i < c1; ++i) eq_cnt += (keys[i] == thr);
+  int tot;
+  int eq_rank = block_scan_excl(eq_cnt, wave_sums, tot);
+  int kept_cnt = 0;
+  for (int i = c0; i < c1; ++i) {
+    const uint32_t key = keys[i];
+    bool kp = key > thr;
+    if (key == thr) {
+      kp = eq_rank < eq_keep;
+      ++eq_rank;
+    }
+    kept_cnt += kp;
+  }
+  int out = block_scan_excl(kept_cnt, wave_sums, tot);
+  eq_rank -= eq_cnt;                              // rewind to the chunk's first equal-keyed rank
+  int first_drop = T;
+  for (int i = c0; i < c1; ++i) {
+    const uint32_t key = keys[i];
+    bool kp = key > thr;
+    if (key == thr) {
+      kp = eq_rank < eq_keep;
+      ++eq_rank;
+    }
+    if (kp) {
+      keep[n + out] = n + i;
+      ++out;
+    } else if (first_drop == T) {
+      first_drop = n + i;
+    }
+  }
+  if (first_drop < T) atomicMin(&sh_p0, first_drop);
+  // first frame and current frame are always kept
+  for (int i = tid; i < n; i += 1024) {
+    keep[i] = i;
+    keep[n + k_keep + i] = t_c + i;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    sel[0] = sh_p0;
+    sel[1] = sh_p0 / g.k_group;
+    sel[3] = tot;                                 // survivors among the middle tokens (= k)
+  }
+}
+
+void launch_select(const KvxBatch& b, hipStream_t st) {
+  hipLaunchKernelGGL(select_kernel, dim3(b.n_items), dim3(1024), 0, st, b);
+}
+
+}  // namespace kvx
