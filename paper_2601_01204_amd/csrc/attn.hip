@@ -42,9 +42,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, y);
 }
 
-// Two fp32 values -> packed f16 (round toward zero; the bias of 2^-12 is far below tolerance).
+// Two fp32 values -> packed f16, round to nearest even (v_cvt_pk_f16_f32).
 __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
-  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+  typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 x = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
 }
 // Two fp32 values -> packed bf16 truncations (hi) and packed bf16 truncated remainders (lo).
 __device__ __forceinline__ void split_bf16(float a, float b, uint32_t& hi, uint32_t& lo) {
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const int item_idx = blockIdx.z / g.n_splits;
   const int split = blockIdx.z % g.n_splits;
-  const Item& it = b.items[item_idx];
+  const Item it = b.items[item_idx];
   const int h = blockIdx.y;
   const int q0 = blockIdx.x * kQTile;
   const int tid = threadIdx.x;
@@ -446,7 +448,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
 // Merge the split-KV partials: out = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
 __global__ __launch_bounds__(256) void combine_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.z];
+  const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
   const int qi = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int c = (threadIdx.x & 15) * 4;

@@ -98,7 +98,7 @@ __device__ __forceinline__ void load_input16(const void* base, int64_t off, int 
 template <int B>
 __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.z];
+  const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
   const int t_c = it.t_c;
   const int t_new = min(t_c + g.n, g.budget);
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
 template <int B>
 __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.z];
+  const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
   const int t_c = it.t_c;
   const int t_new = min(t_c + g.n, g.budget);
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b) {
 // Uncompressed baseline: append the frame's K and V as bf16 rows [H][t_cap][64].
 __global__ __launch_bounds__(256) void append_bf16_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.z];
+  const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
   const int i = blockIdx.x * 32 + (threadIdx.x >> 3);
   const int c8 = (threadIdx.x & 7) * 8;

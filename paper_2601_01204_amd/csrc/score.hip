@@ -13,7 +13,7 @@ namespace kvx {
 // heads 0..H-1 in order starting from zero, divide by H.
 __global__ __launch_bounds__(256) void pool_rows_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.y];
+  const Item it = b.items[blockIdx.y];
   if (!it.prune) return;
   const int row = blockIdx.x;
   int a, e;
@@ -31,10 +31,12 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const KvxBatch b) {
     if (g.in_f32) {
       const float* q = reinterpret_cast<const float*>(it.q);
       acc = q[(int64_t)a * g.tok_stride + (int64_t)h * g.head_stride + c];
+#pragma unroll 8
       for (int t = a + 1; t < e; ++t) acc = acc + q[(int64_t)t * g.tok_stride + (int64_t)h * g.head_stride + c];
     } else {
       const uint16_t* q = reinterpret_cast<const uint16_t*>(it.q);
       acc = __uint_as_float((uint32_t)q[(int64_t)a * g.tok_stride + (int64_t)h * g.head_stride + c] << 16);
+#pragma unroll 8
       for (int t = a + 1; t < e; ++t)
         acc = acc + __uint_as_float((uint32_t)q[(int64_t)t * g.tok_stride + (int64_t)h * g.head_stride + c] << 16);
     }
@@ -53,12 +55,13 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const KvxBatch b) {
 // zero, divide by N_pooled.
 __global__ __launch_bounds__(64) void pool_mean_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.x];
+  const Item it = b.items[blockIdx.x];
   if (!it.prune) return;
   const float* qbar = reinterpret_cast<const float*>(cache_scratch(g, it.cache) + g.sl.qbar);
   float* qt = reinterpret_cast<float*>(cache_scratch(g, it.cache) + g.sl.qt);
   const int c = threadIdx.x;
   float acc = 0.f;
+#pragma unroll 16
   for (int i = 0; i < g.n_pooled; ++i) acc = acc + qbar[i * kHeadDim + c];
   qt[c] = acc / (float)g.n_pooled;
 }
@@ -77,7 +80,7 @@ __device__ __forceinline__ int row_code(const uint32_t* w, int c) {
 template <int B>
 __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.z];
+  const Item it = b.items[blockIdx.z];
   if (!it.prune) return;
   const int h = blockIdx.y;
   const int j0 = blockIdx.x * 256;

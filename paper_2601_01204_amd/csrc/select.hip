@@ -41,7 +41,7 @@ __device__ __forceinline__ int block_scan_excl(int v, int* wave_sums, int& total
 
 __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const Item& it = b.items[blockIdx.x];
+  const Item it = b.items[blockIdx.x];
   if (!it.prune) return;
   const int n = g.n, t_c = it.t_c, H = g.H;
   const int M = t_c - n;                 // middle tokens: cache positions n .. t_c - 1
@@ -61,6 +61,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
   __shared__ uint32_t sh_prefix;
   __shared__ int sh_remaining;
   __shared__ int sh_p0;
+  __shared__ int sh_eq;
 
   // S_j = (D[0,j] + D[1,j] + ... + D[H-1,j]) / H, heads added in order (Eq. 4-6).
   for (int i = tid; i < M; i += 1024) {
@@ -89,22 +90,25 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
       if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
     }
     __syncthreads();
-    if (tid == 0) {
-      int rem = sh_remaining, bin = 0;
-      while (bin < 255 && hist[bin] < rem) {
-        rem -= hist[bin];
-        ++bin;
+    {
+      // the bin holding the rem-th smallest candidate: inclusive counts by a block scan over the 256 bins
+      const int cnt = tid < 256 ? hist[tid] : 0;
+      int tot_unused;
+      const int before = block_scan_excl(cnt, wave_sums, tot_unused);
+      const int rem = sh_remaining;
+      __syncthreads();
+      if (tid < 256 && before < rem && before + cnt >= rem) {
+        sh_remaining = rem - before;
+        sh_prefix = prefix | ((uint32_t)tid << shift);
+        sh_eq = cnt;                                 // after the last pass: keys equal to the threshold
       }
-      sh_remaining = rem;
-      sh_prefix = prefix | ((uint32_t)bin << shift);
-      if (pass == 0) hist[0] = hist[bin];        // number of keys equal to the threshold
     }
     mask |= 0xFFu << shift;
     __syncthreads();
   }
   const uint32_t thr = sh_prefix;
   const int need_eq = sh_remaining;              // equal-keyed tokens to drop (highest positions first)
-  const int total_eq = hist[0];
+  const int total_eq = sh_eq;
   const int eq_keep = total_eq - need_eq;        // equal-keyed tokens kept: the eq_keep lowest positions
   __syncthreads();
 
