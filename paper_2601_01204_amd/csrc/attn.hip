@@ -6,19 +6,28 @@
 // the 256 threads de-quantise the K and V codes once into LDS (K row-major, V
 // transposed), then every wave runs S^T = K Q^T and O^T += V^T P^T on the matrix cores
 // with an online softmax in registers.  Computing the transposed products puts a query
-// in a lane and its keys in that lane's registers, so row max / row sum need one
-// cross-lane exchange and the probabilities feed the second MFMA straight from
-// registers (the key order inside a 16-key step is a permutation shared by V^T's LDS
-// layout).
+// in a lane and its keys in that lane's registers, so the probabilities feed the second
+// MFMA straight from registers (the key order inside a 16-key step is a permutation
+// shared by V^T's LDS layout) and the row statistics stay in the lane.
 //
 // Precision.  A de-quantised key s * (code - z) is an fp32 value; rounding it to 8
 // significand bits perturbs the logits of the dominant key channels by ~1e-2, far above
 // the output tolerance.  K~ is therefore held as a bf16 pair hi + lo (hi = truncation,
 // lo = truncated remainder, together 16 significand bits) and S^T takes two bf16 MFMAs
-// (v_mfma_f32_32x32x16_bf16) against the exact bf16 queries; bf16 keys of the frame
-// itself have lo = 0 and take one.  P (in [0, 1]) and V~ go through the f16 MFMA
-// (v_mfma_f32_32x32x16_f16, 11 significand bits, same rate).  fp32 inputs are split the
-// same way (queries too).
+// (v_mfma_f32_32x32x16_bf16) against the exact bf16 queries.  P and V~ go through the
+// f16 MFMA (v_mfma_f32_32x32x16_f16, 11 significand bits, same rate).  fp32 inputs are
+// split the same way (queries too).
+//
+// Softmax.  The softmax scale times log2(e) is folded into the keys as they are staged,
+// so S^T is already in log2 units.  Each query keeps a reference m that is raised only
+// when a key exceeds it by more than kRescaleGap (then O and l are rescaled, a rare,
+// wave-uniform branch); otherwise p = 2^(s - m) <= 2^kRescaleGap needs no rescale.
+//
+// Schedule.  A wave issues instructions in order, so MFMAs only overlap vector work that
+// sits between them in program order: the 32-key halves of a tile are software-pipelined
+// (QK of the second half with the softmax of the first, PV of the first with the softmax
+// of the second, PV of the second followed by the staging of the next tile) and
+// sched_barrier fences keep that interleaving.
 #include "kvx_dev.h"
 
 namespace kvx {
@@ -26,25 +35,25 @@ namespace kvx {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kLdsRow = 72;                       // bf16 elements per LDS row: 64 + 8 pad (144 B)
+constexpr int kLdsRow = 72;                       // 16-bit elements per LDS row: 64 + 8 pad (144 B)
 constexpr int kTileElems = kTileK * kLdsRow;      // one K or V^T tile
 constexpr float kNegBig = -1.0e30f;
+constexpr float kRescaleGap = 8.0f;               // log2 units
+
+#define KVX_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 __device__ __forceinline__ int swap23(int x) { return (x & ~0xC) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  f32x2 x = {a, b};
-  bf16x2 y = __builtin_convertvector(x, bf16x2);
-  return __builtin_bit_cast(uint32_t, y);
+  const f32x2 x = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
-
 // Two fp32 values -> packed f16, round to nearest even (v_cvt_pk_f16_f32).
 __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
-  typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
   const f32x2 x = {a, b};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
 }
@@ -74,7 +83,7 @@ __device__ __forceinline__ void load_octet(const uint8_t* p, uint32_t (&w)[2]) {
     w[0] = *reinterpret_cast<const uint16_t*>(p);
     w[1] = 0;
   } else {
-    uint2 t = *reinterpret_cast<const uint2*>(p);
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
     w[0] = t.x;
     w[1] = t.y;
   }
@@ -89,7 +98,7 @@ struct TileRaw {
   uint32_t vc[2][2];
   VMeta vm[2];
   // rows of the frame itself or of the uncompressed cache: two keys x eight channels
-  uint4 ok[2], ov[2];                          // packed bf16
+  uint4 ok[2], ov[2];                                     // packed bf16
   float ok32[F32IN ? 2 : 1][8], ov32[F32IN ? 2 : 1][8];   // fp32 inputs
 };
 
@@ -128,6 +137,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
 
   const uint8_t* half = cache_half(g, it.cache, it.cur);
   const bool compressed = !g.uncompressed;
+  const float sc = g.scale_log2;
+  // a wave whose 64 query rows all lie past the frame only helps with staging
+  const bool wave_active = (q0 + wave * 64) < n;
 
   // ---- this wave's query fragments (B operand of S^T = K Q^T) ---------------------
   bf16x8 qf[2][4];
@@ -154,11 +166,11 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
     }
   }
 
-  f32x16 o[2][2];
-  float m_run[2], l_run[2];
+  f32x16 o[2][2];                     // [channel block][query block]
+  float m_ref[2], l_run[2];           // per query block; lanes l and l + 32 hold the same m_ref
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    m_run[nb] = kNegBig;
+    m_ref[nb] = kNegBig;
     l_run[nb] = 0.f;
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
@@ -186,8 +198,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
       const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + co * 8;
       const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(half + g.lay.k_scale) + moff);
       const int4* zp = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(half + g.lay.k_zero) + moff);
-      float4 s0 = sp[0], s1 = sp[1];
-      int4 z0 = zp[0], z1 = zp[1];
+      const float4 s0 = sp[0], s1 = sp[1];
+      const int4 z0 = zp[0], z1 = zp[1];
       raw.ks[0] = s0.x; raw.ks[1] = s0.y; raw.ks[2] = s0.z; raw.ks[3] = s0.w;
       raw.ks[4] = s1.x; raw.ks[5] = s1.y; raw.ks[6] = s1.z; raw.ks[7] = s1.w;
       raw.kz[0] = z0.x; raw.kz[1] = z0.y; raw.kz[2] = z0.z; raw.kz[3] = z0.w;
@@ -229,8 +241,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
     }
   };
 
-  // K: rows (key_a + i) get 8 channels of hi (and lo) as one 16-byte store each.
-  // V: rows are channels; the two keys land side by side as one 4-byte store per channel.
+  // K: row (key_a + i) gets 8 channels of hi and lo as one 16-byte store each; the values
+  // carry the softmax scale.  V: rows are channels; the two keys land side by side as one
+  // 4-byte store per channel.
   auto store_k_split = [&](int buf, int i, const float (&x)[8]) {
     uint32_t hi[4], lo[4];
 #pragma unroll
@@ -243,20 +256,27 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
     for (int e = 0; e < 8; ++e) *reinterpret_cast<uint32_t*>(lds_v[buf] + (co * 8 + e) * kLdsRow + 2 * kp) = pack_f16(a[e], c[e]);
   };
 
+  // De-quantise / convert the raw registers of `tile` into LDS buffer `buf`.
   auto decode_store = [&](int tile, int buf) {
     if (tile < ntc && compressed) {
       const int ja = tile * kTileK + key_a;
+      const bool full = (tile + 1) * kTileK <= t_c;
+      float sk[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sk[e] = raw.ks[e] * sc;
       float va[8], vb[8];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const bool ok = (ja + i) < t_c;
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float kd = raw.ks[e] * (float)(code_at<KB>(raw.kc[i], e) - raw.kz[e]);
-          x[e] = ok ? kd : 0.f;
+          x[e] = sk[e] * (float)(code_at<KB>(raw.kc[i], e) - raw.kz[e]);
           const float vd = raw.vm[i].s * (float)(code_at<VB>(raw.vc[i], e) - raw.vm[i].z);
-          if (i == 0) va[e] = ok ? vd : 0.f; else vb[e] = ok ? vd : 0.f;
+          if (i == 0) va[e] = vd; else vb[e] = vd;
+        }
+        if (!full && (ja + i) >= t_c) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { x[e] = 0.f; if (i == 0) va[e] = 0.f; else vb[e] = 0.f; }
         }
         store_k_split(buf, i, x);
       }
@@ -266,8 +286,11 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
       if (tile < ntc) { base_row = tile * kTileK; limit = t_c; } else { base_row = (tile - ntc) * kTileK; limit = n; }
       if (F32IN && tile >= ntc) {
         if constexpr (F32IN) {
-          store_k_split(buf, 0, raw.ok32[0]);     // rows past the end were loaded as zeros
-          store_k_split(buf, 1, raw.ok32[1]);
+          float x0[8], x1[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { x0[e] = raw.ok32[0][e] * sc; x1[e] = raw.ok32[1][e] * sc; }   // rows past the end are zeros
+          store_k_split(buf, 0, x0);
+          store_k_split(buf, 1, x1);
           store_v_pair(buf, raw.ov32[0], raw.ov32[1]);
         }
       } else {
@@ -276,7 +299,11 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
         for (int i = 0; i < 2; ++i) {
           uint4 kk = raw.ok[i], vv = raw.ov[i];
           if (base_row + key_a + i >= limit) { kk = make_uint4(0, 0, 0, 0); vv = make_uint4(0, 0, 0, 0); }
-          *reinterpret_cast<uint4*>(lds_khi[buf] + (key_a + i) * kLdsRow + co * 8) = kk;      // bf16 keys are exact: no lo part
+          const uint32_t k4[4] = {kk.x, kk.y, kk.z, kk.w};
+          float x[8];
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) { x[2 * e2] = bf16lo_to_f32(k4[e2]) * sc; x[2 * e2 + 1] = bf16hi_to_f32(k4[e2]) * sc; }
+          store_k_split(buf, i, x);
           const uint32_t w4[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
           for (int e2 = 0; e2 < 4; ++e2) {
@@ -289,108 +316,81 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
     }
   };
 
-  auto compute = [&](int tile, int buf) {
-    const uint16_t* lkh = lds_khi[buf];
-    const uint16_t* lkl = lds_klo[buf];
-    const uint16_t* lv = lds_v[buf];
-    int valid;
-    bool has_lo;
-    if (tile < ntc) { valid = min(kTileK, t_c - tile * kTileK); has_lo = compressed; }
-    else { valid = min(kTileK, n - (tile - ntc) * kTileK); has_lo = F32IN; }
+  // ---- pieces of the per-tile pipeline ---------------------------------------------
+  f32x16 s[2][2];                     // [key half][query block], log2-domain logits
+  f16x8 pb[2][2][2];                  // [key half][query block][16-key step]: P^T as B operand
 
-    f32x16 s[2][2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[mb][nb][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        const int aoff = (mb * 32 + l32) * kLdsRow + ks * 16 + hf * 8;
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(lkh + aoff);
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[mb][nb], 0, 0, 0);
-        if constexpr (F32IN) {
-#pragma unroll
-          for (int nb = 0; nb < 2; ++nb) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qlo[nb][ks], s[mb][nb], 0, 0, 0);
-        }
-      }
-    }
-    if (has_lo) {
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(lkl + (mb * 32 + l32) * kLdsRow + ks * 16 + hf * 8);
-#pragma unroll
-          for (int nb = 0; nb < 2; ++nb) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[mb][nb], 0, 0, 0);
-        }
-      }
-    }
+  // Mask the keys past `valid` (ragged last tile) and raise the references if needed.
+  auto pre_softmax = [&](int mb, int valid) {
     if (valid < kTileK) {
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = mb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          if (key >= valid) {
-            s[mb][0][r] = kNegBig;
-            s[mb][1][r] = kNegBig;
-          }
+      for (int r = 0; r < 16; ++r) {
+        const int key = mb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (key >= valid) {
+          s[mb][0][r] = kNegBig;
+          s[mb][1][r] = kNegBig;
         }
+      }
     }
-
-    f16x8 pb[2][4];
-    const float sc = g.scale_log2;
+    float mx[2];
+    bool need = false;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-      float mx = s[0][nb][0];
+      float a = fmaxf(fmaxf(s[mb][nb][0], s[mb][nb][1]), s[mb][nb][2]);
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mb][nb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[nb], mx * sc);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-      m_run[nb] = m_new;
-      float rs = 0.f;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][nb][r], sc, -m_new));
-          rs += p;
-          s[mb][nb][r] = p;
-        }
-      }
-      l_run[nb] = l_run[nb] * alpha + rs;
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[cb][nb][r] *= alpha;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int mb = kk >> 1, r0 = (kk & 1) * 8;
-        const uint4 w = make_uint4(pack_f16(s[mb][nb][r0 + 0], s[mb][nb][r0 + 1]), pack_f16(s[mb][nb][r0 + 2], s[mb][nb][r0 + 3]),
-                                   pack_f16(s[mb][nb][r0 + 4], s[mb][nb][r0 + 5]), pack_f16(s[mb][nb][r0 + 6], s[mb][nb][r0 + 7]));
-        pb[nb][kk] = __builtin_bit_cast(f16x8, w);
-      }
+      for (int r = 3; r < 15; r += 2) a = fmaxf(fmaxf(a, s[mb][nb][r]), s[mb][nb][r + 1]);
+      a = fmaxf(a, s[mb][nb][15]);
+      mx[nb] = a;
+      need |= a > m_ref[nb] + kRescaleGap;
     }
+    if (__any(need)) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+      for (int nb = 0; nb < 2; ++nb) {
+        const float mq = fmaxf(mx[nb], __shfl_xor(mx[nb], 32));      // both halves of a query agree
+        const float m_new = (mq > m_ref[nb] + kRescaleGap) ? mq : m_ref[nb];
+        const float alpha = __builtin_amdgcn_exp2f(m_ref[nb] - m_new);
+        m_ref[nb] = m_new;
+        l_run[nb] *= alpha;
+        if (mb == 1) {
+          // the first half's probabilities are already packed relative to the old reference
+          // and not yet multiplied into O: bring them to the new reference too
+          const _Float16 ah = (_Float16)alpha;
+          pb[0][nb][0] = pb[0][nb][0] * ah;
+          pb[0][nb][1] = pb[0][nb][1] * ah;
+        }
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        const f16x8 a = *reinterpret_cast<const f16x8*>(lv + (cb * 32 + l32) * kLdsRow + kk * 16 + hf * 8);
+        for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[nb][kk], o[cb][nb], 0, 0, 0);
+          for (int r = 0; r < 16; ++r) o[cb][nb][r] *= alpha;
       }
     }
   };
 
-  // ---- tile loop: global loads for tile t+1 are in flight while tile t is computed --
+  // Elements [r0, r0 + cnt) of half mb, query block nb: p = 2^(s - m), packed to f16, summed.
+  const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+  auto softmax_part = [&](int mb, int nb, int r0, int cnt, uint32_t* pk) {
+#pragma unroll
+    for (int r = r0; r < r0 + cnt; r += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(s[mb][nb][r] - m_ref[nb]);
+      const float p1 = __builtin_amdgcn_exp2f(s[mb][nb][r + 1] - m_ref[nb]);
+      const uint32_t w = pack_f16(p0, p1);
+      pk[r >> 1] = w;
+      l_run[nb] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), ones, l_run[nb], false);
+    }
+  };
+  auto finish_p = [&](int mb, int nb, const uint32_t* pk) {
+    pb[mb][nb][0] = __builtin_bit_cast(f16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+    pb[mb][nb][1] = __builtin_bit_cast(f16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
+  };
+
+  // O^T += V^T[:, 16 keys] P^T[16 keys] for one channel block and both query blocks.
+  auto pv_step = [&](int buf, int mb, int kk, int cb) {
+    const f16x8 a = *reinterpret_cast<const f16x8*>(lds_v[buf] + (cb * 32 + l32) * kLdsRow + (mb * 2 + kk) * 16 + hf * 8);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[mb][nb][kk], o[cb][nb], 0, 0, 0);
+  };
+
+  // ---- tile loop --------------------------------------------------------------------
   if (tile_begin < tile_end) {
     load_raw(tile_begin);
     decode_store(tile_begin, 0);
@@ -398,10 +398,96 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
     for (int t = tile_begin; t < tile_end; ++t) {
       const int buf = (t - tile_begin) & 1;
       const bool more = (t + 1) < tile_end;
-      if (more) load_raw(t + 1);
-      compute(t, buf);
-      if (more) decode_store(t + 1, buf ^ 1);
-      __syncthreads();
+      if (more && !(g.ablate & 2)) load_raw(t + 1);
+      if (wave_active && !(g.ablate & 32)) {
+        int valid;
+        if (t < ntc) valid = min(kTileK, t_c - t * kTileK); else valid = min(kTileK, n - (t - ntc) * kTileK);
+        uint32_t pk0[2][8], pk1[2][8];
+
+        // S^T of the first 32 keys
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[0][nb][r] = 0.f;
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const int aoff = l32 * kLdsRow + ks * 16 + hf * 8;
+          const bf16x8 ah = *reinterpret_cast<const bf16x8*>(lds_khi[buf] + aoff);
+          const bf16x8 al = *reinterpret_cast<const bf16x8*>(lds_klo[buf] + aoff);
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) {
+            s[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qf[nb][ks], s[0][nb], 0, 0, 0);
+            s[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qf[nb][ks], s[0][nb], 0, 0, 0);
+            if constexpr (F32IN) s[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qlo[nb][ks], s[0][nb], 0, 0, 0);
+          }
+        }
+        __builtin_amdgcn_s_setprio(0);
+        pre_softmax(0, valid);
+        KVX_FENCE();
+
+        // S^T of the second 32 keys, interleaved with the softmax of the first.  Each
+        // empty asm below takes the next MFMA's LDS operand, the next softmax chunk's
+        // inputs and the previous chunk's outputs as read-write operands; volatile asms
+        // keep their order, so between two of them sit exactly one MFMA and one chunk
+        // of six vector instructions.
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[1][nb][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const int aoff = (32 + l32) * kLdsRow + ks * 16 + hf * 8;
+          bf16x8 ah = *reinterpret_cast<const bf16x8*>(lds_khi[buf] + aoff);
+          bf16x8 al = *reinterpret_cast<const bf16x8*>(lds_klo[buf] + aoff);
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) {
+            asm volatile("" : "+v"(ah), "+v"(s[0][nb]), "+v"(l_run[nb]));
+            s[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qf[nb][ks], s[1][nb], 0, 0, 0);
+            softmax_part(0, nb, ks * 4, 2, pk0[nb]);
+            asm volatile("" : "+v"(al), "+v"(s[0][nb]), "+v"(l_run[nb]), "+v"(pk0[nb][ks * 2]));
+            s[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qf[nb][ks], s[1][nb], 0, 0, 0);
+            softmax_part(0, nb, ks * 4 + 2, 2, pk0[nb]);
+            asm volatile("" : "+v"(l_run[nb]), "+v"(pk0[nb][ks * 2 + 1]));
+            if constexpr (F32IN) s[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qlo[nb][ks], s[1][nb], 0, 0, 0);
+          }
+        }
+        finish_p(0, 0, pk0[0]);
+        finish_p(0, 1, pk0[1]);
+        KVX_FENCE();
+        pre_softmax(1, valid);
+        KVX_FENCE();
+
+        // PV of the first half, interleaved with the softmax of the second: one MFMA and
+        // one chunk of twelve vector instructions between consecutive asms.
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) {
+            const int step = kk * 2 + cb;
+            f16x8 a = *reinterpret_cast<const f16x8*>(lds_v[buf] + (cb * 32 + l32) * kLdsRow + kk * 16 + hf * 8);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+              asm volatile("" : "+v"(a), "+v"(s[1][nb]), "+v"(l_run[nb]));
+              o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[0][nb][kk], o[cb][nb], 0, 0, 0);
+              softmax_part(1, nb, step * 4, 4, pk1[nb]);
+              asm volatile("" : "+v"(l_run[nb]), "+v"(pk1[nb][step * 2]), "+v"(pk1[nb][step * 2 + 1]));
+            }
+          }
+        finish_p(1, 0, pk1[0]);
+        finish_p(1, 1, pk1[1]);
+        KVX_FENCE();
+
+        // PV of the second half; the staging of the next tile follows
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) pv_step(buf, 1, kk, cb);
+        __builtin_amdgcn_s_setprio(0);
+      }
+      if (more && !(g.ablate & 1)) decode_store(t + 1, buf ^ 1);
+      if (!(g.ablate & 16)) __syncthreads();
     }
   }
 
@@ -428,9 +514,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
             }
           }
       }
-    } else {
+    } else if (qi < n) {
       const int slot = item_idx * g.n_splits + split;
-      const int64_t row = ((int64_t)slot * g.H + h) * g.n_pad + qi;     // qi < n_pad always
+      const int64_t row = ((int64_t)slot * g.H + h) * g.n_pad + qi;
       float* po = g.part_o + row * kHeadDim;
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
@@ -440,7 +526,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
           *reinterpret_cast<float4*>(po + c) =
               make_float4(o[cb][nb][4 * r4 + 0], o[cb][nb][4 * r4 + 1], o[cb][nb][4 * r4 + 2], o[cb][nb][4 * r4 + 3]);
         }
-      if (hf == 0) *reinterpret_cast<float2*>(g.part_ml + row * 2) = make_float2(m_run[nb], l_tot);
+      if (hf == 0) *reinterpret_cast<float2*>(g.part_ml + row * 2) = make_float2(m_ref[nb], l_tot);
     }
   }
 }

@@ -513,6 +513,10 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
     h->splits_override = (int32_t)value;
     return KV_OK;
   }
+  if (!strcmp(name, "attention_ablate")) {
+    h->geo.ablate = (int32_t)value;
+    return KV_OK;
+  }
   if (!strcmp(name, "attention_target_workgroups")) {
     if (value < 1 || value > 65536) return fail(h, KV_E_RANGE, "kv_set_option: attention_target_workgroups out of range");
     h->target_wgs = (int32_t)value;

@@ -68,6 +68,7 @@ struct Geometry {
   int32_t n_splits;
   int32_t n_pad;          // query rows padded to a multiple of kQTile
   float scale_log2;       // softmax scale * log2(e)
+  int32_t ablate;         // timing experiments only: bit mask of pipeline stages to skip (results are wrong when non-zero)
 };
 
 struct Item {
