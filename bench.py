@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=24)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--splits", type=int, default=0, help="override the attention key-range split count")
-    ap.add_argument("--ablate", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--no-overlap", action="store_true", help="run the cache update after attention instead of beside it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -82,8 +82,8 @@ def main():
                      out_dtype=kvx.KV_BF16)
     if args.splits:
         h.set_option("attention_splits", args.splits)
-    if args.ablate:
-        h.set_option("attention_ablate", args.ablate)
+    if args.no_overlap:
+        h.set_option("overlap_update", 0)
 
     # a ring of distinct frames, resident in HBM
     ring = w.frames
@@ -116,7 +116,7 @@ def main():
     t1 = time.perf_counter()
     attn_ms, attn_cnt = h.read_timing()["attention"]
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    assert args.ablate or bool(torch.isfinite(out.float()).all())
+    assert bool(torch.isfinite(out.float()).all())
 
     # per-kernel durations of the whole step (separate pass: the extra events perturb the stream a little)
     h.set_timing(0x7F)

@@ -1,11 +1,12 @@
 // Attention of one frame's queries over [de-quantised cache ; the frame's own K/V]
 // (paper Sec. 3.1 Eq. 1 with the de-quantisation of Sec. 3.3 Eq. 10 fused in).
 //
-// Work decomposition: a workgroup of 4 waves owns 256 query rows of one head and a
-// contiguous range of 64-key tiles (split-KV); each wave owns 64 query rows.  Per tile
-// the 256 threads de-quantise the K and V codes once into LDS (K row-major, V
-// transposed), then every wave runs S^T = K Q^T and O^T += V^T P^T on the matrix cores
-// with an online softmax in registers.  Computing the transposed products puts a query
+// Work decomposition: a workgroup of 8 waves owns a tile of query rows of one head (up to
+// 512, cut so that the frame's 32-row blocks spread evenly over tiles and waves) and a
+// contiguous range of 64-key tiles (split-KV); each wave owns one or two 32-row blocks.  Per tile
+// waves 0-3 de-quantise the K codes and waves 4-7 the V codes once into LDS (K
+// row-major, V transposed), then every wave runs S^T = K Q^T and O^T += V^T P^T on the
+// matrix cores with an online softmax in registers.  Computing the transposed products puts a query
 // in a lane and its keys in that lane's registers, so the probabilities feed the second
 // MFMA straight from registers (the key order inside a 16-key step is a permutation
 // shared by V^T's LDS layout) and the row statistics stay in the lane.
@@ -23,12 +24,14 @@
 // when a key exceeds it by more than kRescaleGap (then O and l are rescaled, a rare,
 // wave-uniform branch); otherwise p = 2^(s - m) <= 2^kRescaleGap needs no rescale.
 //
-// Schedule.  A wave issues instructions in order, so MFMAs only overlap vector work that
-// sits between them in program order: the 32-key halves of a tile are software-pipelined
-// (QK of the second half with the softmax of the first, PV of the first with the softmax
-// of the second, PV of the second followed by the staging of the next tile) and
-// sched_barrier fences keep that interleaving.
+// Schedule.  Measured on gfx950, an MFMA overlaps only one or two vector instructions of
+// its own wave but ~20 of its 32 cycles with vector work of the other wave on the SIMD.
+// The two waves a SIMD gets from this workgroup (w and w + 4) therefore run the tile in
+// opposite phase: waves 0-3 compute then stage the next tile, waves 4-7 stage then
+// compute, so one wave's MFMA stretch meets the other's vector stretch.
 #include "kvx_dev.h"
+
+#include <type_traits>
 
 namespace kvx {
 
@@ -91,15 +94,14 @@ __device__ __forceinline__ void load_octet(const uint8_t* p, uint32_t (&w)[2]) {
 
 template <bool F32IN>
 struct TileRaw {
-  // cache tile: two keys x eight channels of codes, the channels' key metadata, the keys' value metadata
-  uint32_t kc[2][2];
-  float ks[8];
-  int32_t kz[8];
-  uint32_t vc[2][2];
-  VMeta vm[2];
-  // rows of the frame itself or of the uncompressed cache: two keys x eight channels
-  uint4 ok[2], ov[2];                                     // packed bf16
-  float ok32[F32IN ? 2 : 1][8], ov32[F32IN ? 2 : 1][8];   // fp32 inputs
+  // Staging registers of one thread: two rows x eight channels of K (waves 0-3) or of V
+  // (waves 4-7).  Cache tile: codes plus metadata (K: the eight channels' scale and
+  // zero-point; V: the two rows' scale and zero-point in s[0..1], z[0..1]).
+  uint32_t c[2][2];
+  float s[8];
+  int32_t z[8];
+  uint4 row[2];                         // bf16 rows (own frame, uncompressed cache)
+  float row32[F32IN ? 2 : 1][8];        // fp32 rows (own frame)
 };
 
 __device__ __forceinline__ void load8_f32(const void* base, int64_t off, float (&x)[8]) {
@@ -109,13 +111,16 @@ __device__ __forceinline__ void load8_f32(const void* base, int64_t off, float (
 }
 
 template <int KB, int VB, bool F32IN>
-__global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
+__global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  const int item_idx = blockIdx.z / g.n_splits;
-  const int split = blockIdx.z % g.n_splits;
+  // linear block id -> (query tile, item, split, head); the last query tile (usually a
+  // ragged, light one) is dispatched last so it fills in behind the full ones
+  int bid = blockIdx.x;
+  const int h = bid % g.H; bid /= g.H;
+  const int split = bid % g.n_splits; bid /= g.n_splits;
+  const int item_idx = bid % b.n_items; bid /= b.n_items;
+  const int qt = bid;
   const Item it = b.items[item_idx];
-  const int h = blockIdx.y;
-  const int q0 = blockIdx.x * kQTile;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -138,15 +143,23 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
   const uint8_t* half = cache_half(g, it.cache, it.cur);
   const bool compressed = !g.uncompressed;
   const float sc = g.scale_log2;
-  // a wave whose 64 query rows all lie past the frame only helps with staging
-  const bool wave_active = (q0 + wave * 64) < n;
+  // Query rows of this wave: the tile's q_blocks 32-row blocks are dealt to the 8 waves as
+  // evenly as possible (one or two blocks each), so ragged frame sizes load the SIMDs evenly.
+  const int blk_base = g.q_blocks >> 3, blk_extra = g.q_blocks & 7;
+  const int blk0 = wave * blk_base + min(wave, blk_extra);
+  const int row0 = (qt * g.q_blocks + blk0) * 32;
+  int nblk = blk_base + (wave < blk_extra ? 1 : 0);
+  if (row0 + 32 >= n) nblk = min(nblk, 1);
+  if (row0 >= n) nblk = 0;                        // such a wave only helps with staging
+  const bool stage_first = wave >= 4;      // waves 4-7 stage the next tile before computing
+  const bool role_k = wave < 4;            // waves 0-3 stage K, waves 4-7 stage V
 
   // ---- this wave's query fragments (B operand of S^T = K Q^T) ---------------------
   bf16x8 qf[2][4];
   bf16x8 qlo[F32IN ? 2 : 1][4];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    const int qi = q0 + wave * 64 + nb * 32 + l32;
+    const int qi = (nb < nblk) ? row0 + nb * 32 + l32 : n;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int64_t off = (int64_t)qi * g.tok_stride + (int64_t)h * g.head_stride + ks * 16 + hf * 8;
@@ -178,9 +191,10 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
       for (int r = 0; r < 16; ++r) o[cb][nb][r] = 0.f;
   }
 
-  // staging role of this thread: keys (key_a, key_a + 1) of the tile, channels [8 co, 8 co + 8)
-  const int kp = tid & 31;
-  const int co = tid >> 5;
+  // staging role of this thread: rows (key_a, key_a + 1) of the tile, channels [8 co, 8 co + 8)
+  const int st = tid & 255;
+  const int kp = st & 31;
+  const int co = st >> 5;
   const int key_a = swap23(2 * kp);
   constexpr int kKRow = 8 * KB;     // bytes per cached key row
   constexpr int kVRow = 8 * VB;
@@ -188,54 +202,53 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
 
   TileRaw<F32IN> raw;
 
-  auto load_raw = [&](int tile) {
+  auto load_raw = [&](int tile) __attribute__((always_inline)) {
     if (tile < ntc && compressed) {
       const int ja = tile * kTileK + key_a;
-      const uint8_t* kcp = half + g.lay.k_codes + ((int64_t)h * g.t_cap + ja) * kKRow + co * KB;
-      load_octet<KB>(kcp, raw.kc[0]);
-      load_octet<KB>(kcp + kKRow, raw.kc[1]);
-      const int grp = ja / g.k_group;
-      const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + co * 8;
-      const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(half + g.lay.k_scale) + moff);
-      const int4* zp = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(half + g.lay.k_zero) + moff);
-      const float4 s0 = sp[0], s1 = sp[1];
-      const int4 z0 = zp[0], z1 = zp[1];
-      raw.ks[0] = s0.x; raw.ks[1] = s0.y; raw.ks[2] = s0.z; raw.ks[3] = s0.w;
-      raw.ks[4] = s1.x; raw.ks[5] = s1.y; raw.ks[6] = s1.z; raw.ks[7] = s1.w;
-      raw.kz[0] = z0.x; raw.kz[1] = z0.y; raw.kz[2] = z0.z; raw.kz[3] = z0.w;
-      raw.kz[4] = z1.x; raw.kz[5] = z1.y; raw.kz[6] = z1.z; raw.kz[7] = z1.w;
-      const uint8_t* vcp = half + g.lay.v_codes + ((int64_t)h * g.t_cap + ja) * kVRow + co * VB;
-      load_octet<VB>(vcp, raw.vc[0]);
-      load_octet<VB>(vcp + kVRow, raw.vc[1]);
-      const VMeta* vmp = reinterpret_cast<const VMeta*>(half + g.lay.v_meta) + ((int64_t)h * g.t_cap + ja) * ngv + (co * 8) / g.v_group;
-      raw.vm[0] = vmp[0];
-      raw.vm[1] = vmp[ngv];
+      if (role_k) {
+        const uint8_t* kcp = half + g.lay.k_codes + ((int64_t)h * g.t_cap + ja) * kKRow + co * KB;
+        load_octet<KB>(kcp, raw.c[0]);
+        load_octet<KB>(kcp + kKRow, raw.c[1]);
+        const int grp = ja / g.k_group;
+        const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + co * 8;
+        const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(half + g.lay.k_scale) + moff);
+        const int4* zp = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(half + g.lay.k_zero) + moff);
+        const float4 s0 = sp[0], s1 = sp[1];
+        const int4 z0 = zp[0], z1 = zp[1];
+        raw.s[0] = s0.x; raw.s[1] = s0.y; raw.s[2] = s0.z; raw.s[3] = s0.w;
+        raw.s[4] = s1.x; raw.s[5] = s1.y; raw.s[6] = s1.z; raw.s[7] = s1.w;
+        raw.z[0] = z0.x; raw.z[1] = z0.y; raw.z[2] = z0.z; raw.z[3] = z0.w;
+        raw.z[4] = z1.x; raw.z[5] = z1.y; raw.z[6] = z1.z; raw.z[7] = z1.w;
+      } else {
+        const uint8_t* vcp = half + g.lay.v_codes + ((int64_t)h * g.t_cap + ja) * kVRow + co * VB;
+        load_octet<VB>(vcp, raw.c[0]);
+        load_octet<VB>(vcp + kVRow, raw.c[1]);
+        const VMeta* vmp = reinterpret_cast<const VMeta*>(half + g.lay.v_meta) + ((int64_t)h * g.t_cap + ja) * ngv + (co * 8) / g.v_group;
+        const VMeta m0 = vmp[0], m1 = vmp[ngv];
+        raw.s[0] = m0.s; raw.z[0] = m0.z;
+        raw.s[1] = m1.s; raw.z[1] = m1.z;
+      }
     } else if (tile < ntc) {
       // uncompressed bf16 cache: rows of 64 bf16
       const int ja = tile * kTileK + key_a;
-      const uint16_t* kb = reinterpret_cast<const uint16_t*>(half + g.lay.k_codes) + ((int64_t)h * g.t_cap + ja) * kHeadDim + co * 8;
-      const uint16_t* vb = reinterpret_cast<const uint16_t*>(half + g.lay.v_codes) + ((int64_t)h * g.t_cap + ja) * kHeadDim + co * 8;
-      raw.ok[0] = *reinterpret_cast<const uint4*>(kb);
-      raw.ok[1] = *reinterpret_cast<const uint4*>(kb + kHeadDim);
-      raw.ov[0] = *reinterpret_cast<const uint4*>(vb);
-      raw.ov[1] = *reinterpret_cast<const uint4*>(vb + kHeadDim);
+      const uint16_t* src = reinterpret_cast<const uint16_t*>(half + (role_k ? g.lay.k_codes : g.lay.v_codes)) +
+                            ((int64_t)h * g.t_cap + ja) * kHeadDim + co * 8;
+      raw.row[0] = *reinterpret_cast<const uint4*>(src);
+      raw.row[1] = *reinterpret_cast<const uint4*>(src + kHeadDim);
     } else {
       const int ia = (tile - ntc) * kTileK + key_a;
+      const void* src = role_k ? it.k : it.v;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const bool ok = (ia + i) < n;
         const int64_t off = (int64_t)(ia + i) * g.tok_stride + (int64_t)h * g.head_stride + co * 8;
         if constexpr (F32IN) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) { raw.ok32[i][e] = 0.f; raw.ov32[i][e] = 0.f; }
-          if (ok) { load8_f32(it.k, off, raw.ok32[i]); load8_f32(it.v, off, raw.ov32[i]); }
+          for (int e = 0; e < 8; ++e) raw.row32[i][e] = 0.f;
+          if (ok) load8_f32(src, off, raw.row32[i]);
         } else {
-          raw.ok[i] = make_uint4(0, 0, 0, 0);
-          raw.ov[i] = make_uint4(0, 0, 0, 0);
-          if (ok) {
-            raw.ok[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.k) + off);
-            raw.ov[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.v) + off);
-          }
+          raw.row[i] = make_uint4(0, 0, 0, 0);
+          if (ok) raw.row[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(src) + off);
         }
       }
     }
@@ -257,244 +270,205 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const KvxBatch b) {
   };
 
   // De-quantise / convert the raw registers of `tile` into LDS buffer `buf`.
-  auto decode_store = [&](int tile, int buf) {
+  auto decode_store = [&](int tile, int buf, int vbuf) __attribute__((always_inline)) {
     if (tile < ntc && compressed) {
       const int ja = tile * kTileK + key_a;
       const bool full = (tile + 1) * kTileK <= t_c;
-      float sk[8];
+      if (role_k) {
+        float sk[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sk[e] = raw.ks[e] * sc;
-      float va[8], vb[8];
+        for (int e = 0; e < 8; ++e) sk[e] = raw.s[e] * sc;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        float x[8];
+        for (int i = 0; i < 2; ++i) {
+          float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          x[e] = sk[e] * (float)(code_at<KB>(raw.kc[i], e) - raw.kz[e]);
-          const float vd = raw.vm[i].s * (float)(code_at<VB>(raw.vc[i], e) - raw.vm[i].z);
-          if (i == 0) va[e] = vd; else vb[e] = vd;
-        }
-        if (!full && (ja + i) >= t_c) {
+          for (int e = 0; e < 8; ++e) x[e] = sk[e] * (float)(code_at<KB>(raw.c[i], e) - raw.z[e]);
+          if (!full && (ja + i) >= t_c) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) { x[e] = 0.f; if (i == 0) va[e] = 0.f; else vb[e] = 0.f; }
-        }
-        store_k_split(buf, i, x);
-      }
-      store_v_pair(buf, va, vb);
-    } else {
-      int base_row, limit;
-      if (tile < ntc) { base_row = tile * kTileK; limit = t_c; } else { base_row = (tile - ntc) * kTileK; limit = n; }
-      if (F32IN && tile >= ntc) {
-        if constexpr (F32IN) {
-          float x0[8], x1[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) { x0[e] = raw.ok32[0][e] * sc; x1[e] = raw.ok32[1][e] * sc; }   // rows past the end are zeros
-          store_k_split(buf, 0, x0);
-          store_k_split(buf, 1, x1);
-          store_v_pair(buf, raw.ov32[0], raw.ov32[1]);
+            for (int e = 0; e < 8; ++e) x[e] = 0.f;
+          }
+          store_k_split(buf, i, x);
         }
       } else {
         float va[8], vb[8];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          uint4 kk = raw.ok[i], vv = raw.ov[i];
-          if (base_row + key_a + i >= limit) { kk = make_uint4(0, 0, 0, 0); vv = make_uint4(0, 0, 0, 0); }
-          const uint32_t k4[4] = {kk.x, kk.y, kk.z, kk.w};
-          float x[8];
+        for (int e = 0; e < 8; ++e) {
+          va[e] = raw.s[0] * (float)(code_at<VB>(raw.c[0], e) - raw.z[0]);
+          vb[e] = raw.s[1] * (float)(code_at<VB>(raw.c[1], e) - raw.z[1]);
+        }
+        if (!full) {
 #pragma unroll
-          for (int e2 = 0; e2 < 4; ++e2) { x[2 * e2] = bf16lo_to_f32(k4[e2]) * sc; x[2 * e2 + 1] = bf16hi_to_f32(k4[e2]) * sc; }
-          store_k_split(buf, i, x);
-          const uint32_t w4[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-          for (int e2 = 0; e2 < 4; ++e2) {
-            if (i == 0) { va[2 * e2] = bf16lo_to_f32(w4[e2]); va[2 * e2 + 1] = bf16hi_to_f32(w4[e2]); }
-            else { vb[2 * e2] = bf16lo_to_f32(w4[e2]); vb[2 * e2 + 1] = bf16hi_to_f32(w4[e2]); }
+          for (int e = 0; e < 8; ++e) {
+            if (ja >= t_c) va[e] = 0.f;
+            if (ja + 1 >= t_c) vb[e] = 0.f;
           }
         }
-        store_v_pair(buf, va, vb);
+        store_v_pair(vbuf, va, vb);
+      }
+    } else {
+      int base_row, limit;
+      if (tile < ntc) { base_row = tile * kTileK; limit = t_c; } else { base_row = (tile - ntc) * kTileK; limit = n; }
+      float x0[8], x1[8];
+      if (F32IN && tile >= ntc) {
+        if constexpr (F32IN) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { x0[e] = raw.row32[0][e]; x1[e] = raw.row32[1][e]; }   // rows past the end are zeros
+        }
+      } else {
+        uint4 r0 = raw.row[0], r1 = raw.row[1];
+        if (base_row + key_a >= limit) r0 = make_uint4(0, 0, 0, 0);
+        if (base_row + key_a + 1 >= limit) r1 = make_uint4(0, 0, 0, 0);
+        const uint32_t a4[4] = {r0.x, r0.y, r0.z, r0.w}, b4[4] = {r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+          x0[2 * e2] = bf16lo_to_f32(a4[e2]); x0[2 * e2 + 1] = bf16hi_to_f32(a4[e2]);
+          x1[2 * e2] = bf16lo_to_f32(b4[e2]); x1[2 * e2 + 1] = bf16hi_to_f32(b4[e2]);
+        }
+      }
+      if (role_k) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { x0[e] *= sc; x1[e] *= sc; }
+        store_k_split(buf, 0, x0);
+        store_k_split(buf, 1, x1);
+      } else {
+        store_v_pair(vbuf, x0, x1);
       }
     }
   };
 
-  // ---- pieces of the per-tile pipeline ---------------------------------------------
-  f32x16 s[2][2];                     // [key half][query block], log2-domain logits
-  f16x8 pb[2][2][2];                  // [key half][query block][16-key step]: P^T as B operand
-
-  // Mask the keys past `valid` (ragged last tile) and raise the references if needed.
-  auto pre_softmax = [&](int mb, int valid) {
-    if (valid < kTileK) {
+  // ---- one tile: S^T, then softmax and O^T ---------------------------------------------
+  const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+  auto compute = [&](auto nbc, int t, int kbuf, int vbuf) __attribute__((always_inline)) {
+    constexpr int NB = decltype(nbc)::value;      // query blocks this wave owns: 1 or 2
+    f32x16 s[2][2];                               // [key half][query block], log2-domain logits
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = mb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (key >= valid) {
-          s[mb][0][r] = kNegBig;
-          s[mb][1][r] = kNegBig;
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[mb][nb][r] = 0.f;
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        const int aoff = (mb * 32 + l32) * kLdsRow + ks * 16 + hf * 8;
+        const bf16x8 ah = *reinterpret_cast<const bf16x8*>(lds_khi[kbuf] + aoff);
+        const bf16x8 al = *reinterpret_cast<const bf16x8*>(lds_klo[kbuf] + aoff);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qf[nb][ks], s[mb][nb], 0, 0, 0);
+          s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qf[nb][ks], s[mb][nb], 0, 0, 0);
+          if constexpr (F32IN) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qlo[nb][ks], s[mb][nb], 0, 0, 0);
         }
       }
     }
+    __builtin_amdgcn_s_setprio(0);
+
+    int valid;
+    if (t < ntc) valid = min(kTileK, t_c - t * kTileK); else valid = min(kTileK, n - (t - ntc) * kTileK);
+    // keys past `valid` (ragged last tile) drop out
+    if (valid < kTileK) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = mb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (key >= valid) {
+            s[mb][0][r] = kNegBig;
+            if (NB == 2) s[mb][1][r] = kNegBig;
+          }
+        }
+    }
+    // raise the references where a key exceeds them by more than the gap (rare)
     float mx[2];
     bool need = false;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      float a = fmaxf(fmaxf(s[mb][nb][0], s[mb][nb][1]), s[mb][nb][2]);
+    for (int nb = 0; nb < NB; ++nb) {
+      float a = fmaxf(s[0][nb][0], s[1][nb][0]);
 #pragma unroll
-      for (int r = 3; r < 15; r += 2) a = fmaxf(fmaxf(a, s[mb][nb][r]), s[mb][nb][r + 1]);
-      a = fmaxf(a, s[mb][nb][15]);
+      for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s[0][nb][r]), s[1][nb][r]);
       mx[nb] = a;
       need |= a > m_ref[nb] + kRescaleGap;
     }
     if (__any(need)) {
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
+      for (int nb = 0; nb < NB; ++nb) {
         const float mq = fmaxf(mx[nb], __shfl_xor(mx[nb], 32));      // both halves of a query agree
         const float m_new = (mq > m_ref[nb] + kRescaleGap) ? mq : m_ref[nb];
         const float alpha = __builtin_amdgcn_exp2f(m_ref[nb] - m_new);
         m_ref[nb] = m_new;
         l_run[nb] *= alpha;
-        if (mb == 1) {
-          // the first half's probabilities are already packed relative to the old reference
-          // and not yet multiplied into O: bring them to the new reference too
-          const _Float16 ah = (_Float16)alpha;
-          pb[0][nb][0] = pb[0][nb][0] * ah;
-          pb[0][nb][1] = pb[0][nb][1] * ah;
-        }
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[cb][nb][r] *= alpha;
       }
     }
-  };
-
-  // Elements [r0, r0 + cnt) of half mb, query block nb: p = 2^(s - m), packed to f16, summed.
-  const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-  auto softmax_part = [&](int mb, int nb, int r0, int cnt, uint32_t* pk) {
+    // p = 2^(s - m), packed to f16 as the B operand of the second product, summed into l
+    f16x8 pb[2][4];                   // [query block][16-key step]
 #pragma unroll
-    for (int r = r0; r < r0 + cnt; r += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(s[mb][nb][r] - m_ref[nb]);
-      const float p1 = __builtin_amdgcn_exp2f(s[mb][nb][r + 1] - m_ref[nb]);
-      const uint32_t w = pack_f16(p0, p1);
-      pk[r >> 1] = w;
-      l_run[nb] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), ones, l_run[nb], false);
+    for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int mb = kk >> 1, r0 = (kk & 1) * 8;
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p0 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e] - m_ref[nb]);
+          const float p1 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e + 1] - m_ref[nb]);
+          w[e] = pack_f16(p0, p1);
+          l_run[nb] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w[e]), ones, l_run[nb], false);
+        }
+        pb[nb][kk] = __builtin_bit_cast(f16x8, make_uint4(w[0], w[1], w[2], w[3]));
+      }
     }
-  };
-  auto finish_p = [&](int mb, int nb, const uint32_t* pk) {
-    pb[mb][nb][0] = __builtin_bit_cast(f16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
-    pb[mb][nb][1] = __builtin_bit_cast(f16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
-  };
-
-  // O^T += V^T[:, 16 keys] P^T[16 keys] for one channel block and both query blocks.
-  auto pv_step = [&](int buf, int mb, int kk, int cb) {
-    const f16x8 a = *reinterpret_cast<const f16x8*>(lds_v[buf] + (cb * 32 + l32) * kLdsRow + (mb * 2 + kk) * 16 + hf * 8);
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[mb][nb][kk], o[cb][nb], 0, 0, 0);
+    for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const f16x8 a = *reinterpret_cast<const f16x8*>(lds_v[vbuf] + (cb * 32 + l32) * kLdsRow + kk * 16 + hf * 8);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[nb][kk], o[cb][nb], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+  auto run_compute = [&](int t, int buf) __attribute__((always_inline)) {
+    if (nblk == 2) compute(std::integral_constant<int, 2>{}, t, buf, buf);
+    else if (nblk == 1) compute(std::integral_constant<int, 1>{}, t, buf, buf);
   };
 
   // ---- tile loop --------------------------------------------------------------------
+  // Between two workgroup barriers waves 0-3 compute tile t and then stage tile t+1, waves
+  // 4-7 stage first and then compute, so the two waves of a SIMD are out of step.  A
+  // tile's codes are loaded one interval before they are decoded.
   if (tile_begin < tile_end) {
     load_raw(tile_begin);
-    decode_store(tile_begin, 0);
+    decode_store(tile_begin, 0, 0);
+    if (tile_begin + 1 < tile_end) load_raw(tile_begin + 1);
     __syncthreads();
     for (int t = tile_begin; t < tile_end; ++t) {
       const int buf = (t - tile_begin) & 1;
       const bool more = (t + 1) < tile_end;
-      if (more && !(g.ablate & 2)) load_raw(t + 1);
-      if (wave_active && !(g.ablate & 32)) {
-        int valid;
-        if (t < ntc) valid = min(kTileK, t_c - t * kTileK); else valid = min(kTileK, n - (t - ntc) * kTileK);
-        uint32_t pk0[2][8], pk1[2][8];
-
-        // S^T of the first 32 keys
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s[0][nb][r] = 0.f;
-        __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const int aoff = l32 * kLdsRow + ks * 16 + hf * 8;
-          const bf16x8 ah = *reinterpret_cast<const bf16x8*>(lds_khi[buf] + aoff);
-          const bf16x8 al = *reinterpret_cast<const bf16x8*>(lds_klo[buf] + aoff);
-#pragma unroll
-          for (int nb = 0; nb < 2; ++nb) {
-            s[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qf[nb][ks], s[0][nb], 0, 0, 0);
-            s[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qf[nb][ks], s[0][nb], 0, 0, 0);
-            if constexpr (F32IN) s[0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qlo[nb][ks], s[0][nb], 0, 0, 0);
-          }
-        }
-        __builtin_amdgcn_s_setprio(0);
-        pre_softmax(0, valid);
-        KVX_FENCE();
-
-        // S^T of the second 32 keys, interleaved with the softmax of the first.  Each
-        // empty asm below takes the next MFMA's LDS operand, the next softmax chunk's
-        // inputs and the previous chunk's outputs as read-write operands; volatile asms
-        // keep their order, so between two of them sit exactly one MFMA and one chunk
-        // of six vector instructions.
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s[1][nb][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const int aoff = (32 + l32) * kLdsRow + ks * 16 + hf * 8;
-          bf16x8 ah = *reinterpret_cast<const bf16x8*>(lds_khi[buf] + aoff);
-          bf16x8 al = *reinterpret_cast<const bf16x8*>(lds_klo[buf] + aoff);
-#pragma unroll
-          for (int nb = 0; nb < 2; ++nb) {
-            asm volatile("" : "+v"(ah), "+v"(s[0][nb]), "+v"(l_run[nb]));
-            s[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qf[nb][ks], s[1][nb], 0, 0, 0);
-            softmax_part(0, nb, ks * 4, 2, pk0[nb]);
-            asm volatile("" : "+v"(al), "+v"(s[0][nb]), "+v"(l_run[nb]), "+v"(pk0[nb][ks * 2]));
-            s[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qf[nb][ks], s[1][nb], 0, 0, 0);
-            softmax_part(0, nb, ks * 4 + 2, 2, pk0[nb]);
-            asm volatile("" : "+v"(l_run[nb]), "+v"(pk0[nb][ks * 2 + 1]));
-            if constexpr (F32IN) s[1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qlo[nb][ks], s[1][nb], 0, 0, 0);
-          }
-        }
-        finish_p(0, 0, pk0[0]);
-        finish_p(0, 1, pk0[1]);
-        KVX_FENCE();
-        pre_softmax(1, valid);
-        KVX_FENCE();
-
-        // PV of the first half, interleaved with the softmax of the second: one MFMA and
-        // one chunk of twelve vector instructions between consecutive asms.
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-          for (int cb = 0; cb < 2; ++cb) {
-            const int step = kk * 2 + cb;
-            f16x8 a = *reinterpret_cast<const f16x8*>(lds_v[buf] + (cb * 32 + l32) * kLdsRow + kk * 16 + hf * 8);
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-              asm volatile("" : "+v"(a), "+v"(s[1][nb]), "+v"(l_run[nb]));
-              o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[0][nb][kk], o[cb][nb], 0, 0, 0);
-              softmax_part(1, nb, step * 4, 4, pk1[nb]);
-              asm volatile("" : "+v"(l_run[nb]), "+v"(pk1[nb][step * 2]), "+v"(pk1[nb][step * 2 + 1]));
-            }
-          }
-        finish_p(1, 0, pk1[0]);
-        finish_p(1, 1, pk1[1]);
-        KVX_FENCE();
-
-        // PV of the second half; the staging of the next tile follows
-        __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-          for (int cb = 0; cb < 2; ++cb) pv_step(buf, 1, kk, cb);
-        __builtin_amdgcn_s_setprio(0);
+      if (stage_first) {
+        if (more) decode_store(t + 1, buf ^ 1, buf ^ 1);
+        if (t + 2 < tile_end) load_raw(t + 2);
+        run_compute(t, buf);
+      } else {
+        run_compute(t, buf);
+        if (more) decode_store(t + 1, buf ^ 1, buf ^ 1);
+        if (t + 2 < tile_end) load_raw(t + 2);
       }
-      if (more && !(g.ablate & 1)) decode_store(t + 1, buf ^ 1);
-      if (!(g.ablate & 16)) __syncthreads();
+      __syncthreads();
     }
   }
 
   // ---- epilogue -------------------------------------------------------------------
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    const int qi = q0 + wave * 64 + nb * 32 + l32;
+    const int qi = (nb < nblk) ? row0 + nb * 32 + l32 : n;
     const float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 32);
     if (g.n_splits == 1) {
       if (qi < n) {
@@ -567,9 +541,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const KvxBatch b) {
 template <int KB, int VB>
 static void launch_attn_t(const KvxBatch& b, hipStream_t st) {
   const Geometry& g = b.g;
-  dim3 grid(g.n_pad / kQTile, g.H, b.n_items * g.n_splits);
-  if (g.in_f32) hipLaunchKernelGGL((attn_kernel<KB, VB, true>), grid, dim3(256), 0, st, b);
-  else hipLaunchKernelGGL((attn_kernel<KB, VB, false>), grid, dim3(256), 0, st, b);
+  dim3 grid(g.n_qtiles * g.H * b.n_items * g.n_splits);
+  if (g.in_f32) hipLaunchKernelGGL((attn_kernel<KB, VB, true>), grid, dim3(512), 0, st, b);
+  else hipLaunchKernelGGL((attn_kernel<KB, VB, false>), grid, dim3(512), 0, st, b);
 }
 
 void launch_attention(const KvxBatch& b, int /*max_tiles*/, hipStream_t st) {

@@ -50,8 +50,13 @@ struct kv_handle {
   int64_t bytes_arena = 0, bytes_scratch = 0, bytes_part = 0;
   int32_t slots_cap = 0;
   int32_t splits_override = 0;
-  int32_t target_wgs = 512;
+  int32_t target_wgs = 256;
   int device = 0;
+  // second stream for the score / prune / re-quantise chain, which is independent of the
+  // attention launches of the same step (both only read the current cache half)
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  int32_t overlap = 1;
   std::string err;
   // timing
   uint32_t timing_mask = 0;
@@ -88,7 +93,7 @@ int validate(const kv_config* c) {
   if (c->mode == KV_COMPRESSED) {
     if ((int64_t)c->budget_tokens < 2 * (int64_t)c->tokens_per_frame)
       return fail(nullptr, KV_E_INVAL, "kv_init: budget_tokens must be >= 2 * tokens_per_frame (first and current frame are always kept)");
-    if (c->budget_tokens > (1 << 22)) return fail(nullptr, KV_E_RANGE, "kv_init: budget_tokens too large");
+    if (c->budget_tokens > 32768) return fail(nullptr, KV_E_RANGE, "kv_init: budget_tokens above 32768 is not supported");
     if (!is_bits(c->k_bits) || !is_bits(c->v_bits)) return fail(nullptr, KV_E_INVAL, "kv_init: k_bits and v_bits must be 2, 4 or 8");
     if (c->k_group != 32 && c->k_group != 64) return fail(nullptr, KV_E_INVAL, "kv_init: k_group must be 32 or 64");
     if (c->v_group != 32 && c->v_group != 64) return fail(nullptr, KV_E_INVAL, "kv_init: v_group must be 32 or 64");
@@ -107,7 +112,7 @@ int pick_splits(const kv_handle* h, int n_items, int min_tiles) {
   if (h->splits_override > 0) {
     s = h->splits_override;
   } else {
-    const int base = n_items * g.H * (g.n_pad / kQTile);
+    const int base = n_items * g.H * g.n_qtiles;
     s = (h->target_wgs + base / 2) / base;
   }
   s = std::max(1, std::min(s, (int)kMaxSplits));
@@ -166,7 +171,12 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   g.in_f32 = c.in_dtype == KV_F32;
   g.out_f32 = c.out_dtype == KV_F32;
   g.uncompressed = unc;
-  g.n_pad = (int32_t)align_up(g.n, kQTile);
+  {
+    const int nblocks = (g.n + 31) / 32;
+    g.n_qtiles = (nblocks + 15) / 16;
+    g.q_blocks = (nblocks + g.n_qtiles - 1) / g.n_qtiles;
+    g.n_pad = g.n_qtiles * g.q_blocks * 32;
+  }
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / std::sqrt((float)kHeadDim);
   g.scale_log2 = scale * 1.4426950408889634f;
 
@@ -224,6 +234,12 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   if (hipMemset(h->arena, 0, (size_t)h->bytes_arena) != hipSuccess || hipMemset(h->scratch, 0, (size_t)h->bytes_scratch) != hipSuccess ||
       hipDeviceSynchronize() != hipSuccess) {
     rc = fail(nullptr, KV_E_HIP, "kv_init: clearing the arena failed: %s", hipGetErrorString(hipGetLastError()));
+    kv_destroy(h);
+    return rc;
+  }
+  if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess || hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming) != hipSuccess) {
+    rc = fail(nullptr, KV_E_HIP, "kv_init: creating the side stream failed: %s", hipGetErrorString(hipGetLastError()));
     kv_destroy(h);
     return rc;
   }
@@ -295,6 +311,33 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
     b.g.n_splits = pick_splits(h, cnt, min_tiles);
     if (cnt * b.g.n_splits > h->slots_cap) b.g.n_splits = std::max(1, h->slots_cap / cnt);
 
+    hipStream_t sb = st;          // stream of the cache-update chain
+    if (h->overlap && h->side && !g0.uncompressed) {
+      hipEventRecord(h->ev_fork, st);
+      hipStreamWaitEvent(h->side, h->ev_fork, 0);
+      sb = h->side;
+    }
+    if (g0.uncompressed) {
+      // the baseline appends in place behind the rows attention reads: same stream, after it
+    } else {
+      if (any_prune) {
+        record(h, KV_K_POOL, true, sb);
+        launch_pool(b, sb);
+        record(h, KV_K_POOL, false, sb);
+        record(h, KV_K_SCORE, true, sb);
+        launch_score(b, max_tc, sb);
+        record(h, KV_K_SCORE, false, sb);
+        record(h, KV_K_SELECT, true, sb);
+        launch_select(b, sb);
+        record(h, KV_K_SELECT, false, sb);
+      }
+      record(h, KV_K_REBUILD_K, true, sb);
+      launch_rebuild_k(b, max_tnew, sb);
+      record(h, KV_K_REBUILD_K, false, sb);
+      record(h, KV_K_REBUILD_V, true, sb);
+      launch_rebuild_v(b, max_tnew, sb);
+      record(h, KV_K_REBUILD_V, false, sb);
+    }
     record(h, KV_K_ATTENTION, true, st);
     launch_attention(b, 0, st);
     record(h, KV_K_ATTENTION, false, st);
@@ -305,24 +348,10 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
       record(h, KV_K_REBUILD_V, true, st);
       launch_append_bf16(b, st);
       record(h, KV_K_REBUILD_V, false, st);
-    } else {
-      if (any_prune) {
-        record(h, KV_K_POOL, true, st);
-        launch_pool(b, st);
-        record(h, KV_K_POOL, false, st);
-        record(h, KV_K_SCORE, true, st);
-        launch_score(b, max_tc, st);
-        record(h, KV_K_SCORE, false, st);
-        record(h, KV_K_SELECT, true, st);
-        launch_select(b, st);
-        record(h, KV_K_SELECT, false, st);
-      }
-      record(h, KV_K_REBUILD_K, true, st);
-      launch_rebuild_k(b, max_tnew, st);
-      record(h, KV_K_REBUILD_K, false, st);
-      record(h, KV_K_REBUILD_V, true, st);
-      launch_rebuild_v(b, max_tnew, st);
-      record(h, KV_K_REBUILD_V, false, st);
+    }
+    if (sb != st) {
+      hipEventRecord(h->ev_join, sb);
+      hipStreamWaitEvent(st, h->ev_join, 0);
     }
     hipError_t le = hipGetLastError();
     if (le != hipSuccess) return fail(h, KV_E_HIP, "kv_step: launch failed: %s", hipGetErrorString(le));
@@ -472,6 +501,9 @@ void kv_destroy(kv_handle* h) {
   if (!h) return;
   for (auto& t : h->timed) { hipEventDestroy(t.start); hipEventDestroy(t.stop); }
   for (auto& t : h->free_events) { hipEventDestroy(t.start); hipEventDestroy(t.stop); }
+  if (h->side) { hipStreamSynchronize(h->side); hipStreamDestroy(h->side); }
+  if (h->ev_fork) hipEventDestroy(h->ev_fork);
+  if (h->ev_join) hipEventDestroy(h->ev_join);
   if (h->arena) hipFree(h->arena);
   if (h->scratch) hipFree(h->scratch);
   if (h->part_o) hipFree(h->part_o);
@@ -513,8 +545,8 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
     h->splits_override = (int32_t)value;
     return KV_OK;
   }
-  if (!strcmp(name, "attention_ablate")) {
-    h->geo.ablate = (int32_t)value;
+  if (!strcmp(name, "overlap_update")) {
+    h->overlap = value != 0;
     return KV_OK;
   }
   if (!strcmp(name, "attention_target_workgroups")) {

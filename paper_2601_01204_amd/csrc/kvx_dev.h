@@ -9,7 +9,7 @@ namespace kvx {
 
 constexpr int kHeadDim = 64;        // d; the kernels are written for 64 channels per head
 constexpr int kTileK = 64;          // keys per attention tile / tokens per rebuild block
-constexpr int kQTile = 256;         // query rows per attention workgroup (4 waves x 64)
+constexpr int kQTileMax = 512;      // most query rows per attention workgroup (8 waves x 64)
 constexpr int kMaxItems = 48;       // caches per launch (bounded by the kernel-argument size)
 constexpr int kMaxSplits = 16;      // key-range splits per attention workgroup column
 
@@ -38,7 +38,7 @@ struct ScratchLayout {
   int64_t scores;     // [t_cap] float: importance score of middle tokens (index = cache position - n)
   int64_t keys;       // [t_cap] uint32: order-preserving image of the scores
   int64_t keep;       // [t_cap] int32: kept positions, ascending
-  int64_t sel;        // [16] int32: [0] first dropped position, [1] first rebuilt key group, [2] groups rebuilt (running)
+  int64_t sel;        // [16] int32: [0] first dropped position, [1] first rebuilt key group, [2] groups rebuilt (running), [3] kept middle tokens, [4] pooled-row blocks finished
   int64_t bytes;
 };
 
@@ -66,9 +66,10 @@ struct Geometry {
   int32_t out_f32;        // 1: out is fp32, 0: bf16
   int32_t uncompressed;   // 1: bf16 cache without pruning or quantisation
   int32_t n_splits;
-  int32_t n_pad;          // query rows padded to a multiple of kQTile
+  int32_t n_pad;          // query rows padded to n_qtiles * q_blocks * 32
+  int32_t n_qtiles;       // query tiles (attention workgroups per head and key split)
+  int32_t q_blocks;       // 32-row query blocks per tile (<= 16)
   float scale_log2;       // softmax scale * log2(e)
-  int32_t ablate;         // timing experiments only: bit mask of pipeline stages to skip (results are wrong when non-zero)
 };
 
 struct Item {

@@ -4,12 +4,18 @@
 // order-preserving uint32 image of their fp32 bits, equal scores keep the lower
 // position, so the result is unique and bit-exact.
 //
-// One workgroup of 1024 threads per cache: a 4-pass most-significant-byte-first radix
-// select finds the key of the last token to drop, two block scans resolve ties by
-// position and compact the survivors.
+// One workgroup of 1024 threads per cache.  Each thread keeps its share of the keys in
+// registers (element i of thread t is position t + 1024 i, so the loads coalesce); a
+// 4-pass most-significant-byte-first radix select over LDS histograms finds the key of
+// the last token to drop; keep flags go to LDS and a block scan over contiguous chunks
+// compacts the survivors in position order.
 #include "kvx_dev.h"
 
 namespace kvx {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelPerThread = 32;                              // keys held in registers per thread
+constexpr int kSelMaxM = kSelThreads * kSelPerThread;          // 32768 middle tokens
 
 __device__ __forceinline__ uint32_t order_key(float x) {
   const uint32_t u = __float_as_uint(x);
@@ -39,7 +45,7 @@ __device__ __forceinline__ int block_scan_excl(int v, int* wave_sums, int& total
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.x];
   if (!it.prune) return;
@@ -51,7 +57,6 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
   uint8_t* sc = cache_scratch(g, it.cache);
   const float* dots = reinterpret_cast<const float*>(sc + g.sl.dots);
   float* scores = reinterpret_cast<float*>(sc + g.sl.scores);
-  uint32_t* keys = reinterpret_cast<uint32_t*>(sc + g.sl.keys);
   int32_t* keep = reinterpret_cast<int32_t*>(sc + g.sl.keep);
   int32_t* sel = reinterpret_cast<int32_t*>(sc + g.sl.sel);
   const int tid = threadIdx.x;
@@ -62,14 +67,31 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
   __shared__ int sh_remaining;
   __shared__ int sh_p0;
   __shared__ int sh_eq;
+  __shared__ uint8_t flags[kSelMaxM];
 
   // S_j = (D[0,j] + D[1,j] + ... + D[H-1,j]) / H, heads added in order (Eq. 4-6).
-  for (int i = tid; i < M; i += 1024) {
-    float acc = dots[n + i];
-    for (int h = 1; h < H; ++h) acc = acc + dots[(int64_t)h * g.t_cap + n + i];
-    const float s = acc / (float)H;
-    scores[i] = s;
-    keys[i] = order_key(s);
+  uint32_t key[kSelPerThread];
+#pragma unroll
+  for (int k = 0; k < kSelPerThread; ++k) {
+    const int i = tid + k * kSelThreads;
+    key[k] = 0u;
+    if (i < M) {
+      const float* d0 = dots + n + i;
+      float acc = d0[0];
+      int h = 1;
+      for (; h + 3 < H; h += 4) {      // loads of four heads in flight, additions in head order
+        const float a = d0[(int64_t)h * g.t_cap], c = d0[(int64_t)(h + 1) * g.t_cap];
+        const float e = d0[(int64_t)(h + 2) * g.t_cap], f = d0[(int64_t)(h + 3) * g.t_cap];
+        acc = acc + a;
+        acc = acc + c;
+        acc = acc + e;
+        acc = acc + f;
+      }
+      for (; h < H; ++h) acc = acc + d0[(int64_t)h * g.t_cap];
+      const float s = acc / (float)H;
+      scores[i] = s;
+      key[k] = order_key(s);
+    }
   }
   if (tid == 0) {
     sh_prefix = 0u;
@@ -85,13 +107,14 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
     const uint32_t prefix = sh_prefix;
-    for (int i = tid; i < M; i += 1024) {
-      const uint32_t key = keys[i];
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+#pragma unroll
+    for (int k = 0; k < kSelPerThread; ++k) {
+      const int i = tid + k * kSelThreads;
+      if (i < M && (key[k] & mask) == prefix) atomicAdd(&hist[(key[k] >> shift) & 255u], 1);
     }
     __syncthreads();
     {
-      // the bin holding the rem-th smallest candidate: inclusive counts by a block scan over the 256 bins
+      // the bin holding the rem-th smallest candidate: counts before each bin by a block scan
       const int cnt = tid < 256 ? hist[tid] : 0;
       int tot_unused;
       const int before = block_scan_excl(cnt, wave_sums, tot_unused);
@@ -110,36 +133,35 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
   const int need_eq = sh_remaining;              // equal-keyed tokens to drop (highest positions first)
   const int total_eq = sh_eq;
   const int eq_keep = total_eq - need_eq;        // equal-keyed tokens kept: the eq_keep lowest positions
+
+  // Keep flags: 1 = keep, 0 = drop, 2 = equal to the threshold (resolved by position below).
+#pragma unroll
+  for (int k = 0; k < kSelPerThread; ++k) {
+    const int i = tid + k * kSelThreads;
+    if (i < M) flags[i] = key[k] > thr ? 1 : (key[k] == thr ? (eq_keep == 0 ? 0 : 2) : 0);
+  }
   __syncthreads();
 
   // Contiguous chunk of middle positions per thread, so prefix sums follow position order.
-  const int chunk = (M + 1023) / 1024;
+  const int chunk = (M + kSelThreads - 1) / kSelThreads;
   const int c0 = min(tid * chunk, M), c1 = min(c0 + chunk, M);
-  int eq_cnt = 0;
-  for (int i = c0; i < c1; ++i) eq_cnt += (keys[i] == thr);
   int tot;
-  int eq_rank = block_scan_excl(eq_cnt, wave_sums, tot);
-  int kept_cnt = 0;
-  for (int i = c0; i < c1; ++i) {
-    const uint32_t key = keys[i];
-    bool kp = key > thr;
-    if (key == thr) {
-      kp = eq_rank < eq_keep;
-      ++eq_rank;
-    }
-    kept_cnt += kp;
+  if (eq_keep > 0) {                              // ties straddle the cut: the lowest positions stay
+    int eq_cnt = 0;
+    for (int i = c0; i < c1; ++i) eq_cnt += (flags[i] == 2);
+    int eq_rank = block_scan_excl(eq_cnt, wave_sums, tot);
+    for (int i = c0; i < c1; ++i)
+      if (flags[i] == 2) {
+        flags[i] = eq_rank < eq_keep ? 1 : 0;
+        ++eq_rank;
+      }
   }
+  int kept_cnt = 0;
+  for (int i = c0; i < c1; ++i) kept_cnt += flags[i];
   int out = block_scan_excl(kept_cnt, wave_sums, tot);
-  eq_rank -= eq_cnt;                              // rewind to the chunk's first equal-keyed rank
   int first_drop = T;
   for (int i = c0; i < c1; ++i) {
-    const uint32_t key = keys[i];
-    bool kp = key > thr;
-    if (key == thr) {
-      kp = eq_rank < eq_keep;
-      ++eq_rank;
-    }
-    if (kp) {
+    if (flags[i]) {
       keep[n + out] = n + i;
       ++out;
     } else if (first_drop == T) {
@@ -148,7 +170,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
   }
   if (first_drop < T) atomicMin(&sh_p0, first_drop);
   // first frame and current frame are always kept
-  for (int i = tid; i < n; i += 1024) {
+  for (int i = tid; i < n; i += kSelThreads) {
     keep[i] = i;
     keep[n + k_keep + i] = t_c + i;
   }
@@ -161,7 +183,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const KvxBatch b) {
 }
 
 void launch_select(const KvxBatch& b, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel, dim3(b.n_items), dim3(1024), 0, st, b);
+  hipLaunchKernelGGL(select_kernel, dim3(b.n_items), dim3(kSelThreads), 0, st, b);
 }
 
 }  // namespace kvx
