@@ -176,7 +176,11 @@ int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches);
 
 /* Tuning knobs (not needed for correct results):
  *   "attention_splits"            0 = choose automatically, 1..16 = key-range splits
- *   "attention_target_workgroups" workgroups the automatic choice aims for (default 512) */
+ *   "attention_target_workgroups" workgroups the automatic choice aims for
+ *   "overlap_update"              1 (default): scoring, pruning and re-quantisation run on a
+ *                                 second stream of the library beside attention, joined back
+ *                                 into hip_stream before kv_step returns; 0: everything in
+ *                                 order on hip_stream */
 int kv_set_option(kv_handle* h, const char* name, int64_t value);
 
 #ifdef __cplusplus

@@ -50,7 +50,7 @@ struct kv_handle {
   int64_t bytes_arena = 0, bytes_scratch = 0, bytes_part = 0;
   int32_t slots_cap = 0;
   int32_t splits_override = 0;
-  int32_t target_wgs = 256;
+  int32_t target_wgs = 192;   // three quarters of the CUs: the rest runs the cache-update chain beside attention
   int device = 0;
   // second stream for the score / prune / re-quantise chain, which is independent of the
   // attention launches of the same step (both only read the current cache half)
@@ -547,6 +547,7 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
   }
   if (!strcmp(name, "overlap_update")) {
     h->overlap = value != 0;
+    h->target_wgs = h->overlap ? 192 : 256;
     return KV_OK;
   }
   if (!strcmp(name, "attention_target_workgroups")) {

@@ -1,0 +1,205 @@
+"""GPU tests of the remaining entry points and modes: batched steps, the uncompressed bf16
+baseline cache, strided inputs, determinism, long-run invariants, error paths."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import xstream_oracle as xo
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _small(**kw):
+    base = dict(name="small", n_heads=2, head_dim=64, tokens_per_frame=133, n_special=5, pool_group=16,
+                budget_tokens=500, frames=8, n_layers=1, n_streams=1, k_bits=4, k_group=64, v_bits=4, v_group=64,
+                dtype="bf16", seed=31)
+    base.update(kw)
+    return si.Workload(**base)
+
+
+def test_batched_steps_match_per_cache_oracles():
+    """kv_step_batched over 2 streams x 3 layers: each cache evolves exactly like its own oracle."""
+    import torch
+    w = _small(n_layers=3, n_streams=2)
+    h = pu.make_handle(w, n_streams=2, n_layers=3)
+    caches = {(s, l): xo.OracleCache(pu.oracle_cfg(w)) for s in range(2) for l in range(3)}
+    sig = {k: si.key_channel_scales(w, *k) for k in caches}
+    for t in range(7):
+        items, refs, outs = [], {}, {}
+        for (s, l), cache in caches.items():
+            q, k, v = si.frame_qkv(w, t, s, l, sig[(s, l)])
+            refs[(s, l)] = cache.step(q, k, v)
+            tq, tk, tv = (pu.to_device(a, w) for a in (q, k, v))
+            out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+            outs[(s, l)] = out
+            items.append((s, l, tq, tk, tv, out))
+        h.step_batched(items)
+        torch.cuda.synchronize()
+        for key, cache in caches.items():
+            pu.check_output(outs[key].cpu().numpy(), refs[key], f"batched frame {t} cache {key}")
+            pu.check_state(h.export(*key), cache, f"batched frame {t} cache {key}")
+    st = h.stats()
+    assert st["n_caches"] == 6 and st["frames_seen_total"] == 42
+    assert st["cache_len_min"] == st["cache_len_max"] == 500
+    h.close()
+
+
+def test_batched_caches_at_different_lengths():
+    """Caches of one batch may be at different frame counts (one prunes, the other does not)."""
+    import torch
+    w = _small(n_streams=2)
+    h = pu.make_handle(w, n_streams=2)
+    caches = [xo.OracleCache(pu.oracle_cfg(w)) for _ in range(2)]
+    sig = [si.key_channel_scales(w, s, 0) for s in range(2)]
+    frame = [0, 0]
+
+    def feed(streams):
+        items, chk = [], []
+        for s in streams:
+            q, k, v = si.frame_qkv(w, frame[s], s, 0, sig[s])
+            ref = caches[s].step(q, k, v)
+            tq, tk, tv = (pu.to_device(a, w) for a in (q, k, v))
+            out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+            items.append((s, 0, tq, tk, tv, out))
+            chk.append((s, out, ref))
+            frame[s] += 1
+        h.step_batched(items)
+        torch.cuda.synchronize()
+        for s, out, ref in chk:
+            pu.check_output(out.cpu().numpy(), ref, f"stream {s} frame {frame[s] - 1}")
+            pu.check_state(h.export(s, 0), caches[s], f"stream {s} frame {frame[s] - 1}")
+
+    for _ in range(3):
+        feed([0])                 # stream 0 runs ahead: 3 frames, 399 tokens
+    for _ in range(4):
+        feed([0, 1])              # stream 0 prunes from its 4th frame on, stream 1 is still filling
+    h.close()
+
+
+def test_uncompressed_baseline_matches_full_attention():
+    """KV_UNCOMPRESSED_BF16: a growing bf16 cache, no pruning, no quantisation = plain Eq. 1."""
+    import torch
+    import paper_2601_01204_amd as kvx
+    w = _small()
+    h = pu.make_handle(w, mode=kvx.KV_UNCOMPRESSED_BF16, max_frames=6)
+    sigma = si.key_channel_scales(w)
+    frames = [si.frame_qkv(w, t, sigma=sigma) for t in range(6)]
+    for t, (q, k, v) in enumerate(frames):
+        tq, tk, tv = (pu.to_device(a, w) for a in (q, k, v))
+        out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+        h.step(tq, tk, tv, out)
+        torch.cuda.synchronize()
+        ref = xo.reference_full_attention(frames, t, 1.0 / 8.0)
+        pu.check_output(out.cpu().numpy(), ref, f"uncompressed frame {t}")
+    st = h.stats()
+    assert st["cache_len_max"] == 6 * w.tokens_per_frame
+    tq, tk, tv = (pu.to_device(a, w) for a in frames[0])
+    with pytest.raises(kvx.KvError) as e:          # the cache is full: max_frames reached
+        h.step(tq, tk, tv, torch.empty(tq.shape, dtype=torch.float32, device=tq.device))
+    assert e.value.code == -4
+    h.close()
+
+
+def test_strided_inputs():
+    """q, k, v, out as slices of a fused [n, 3 + 1, H, d] buffer (non-trivial token stride)."""
+    import torch
+    w = _small(frames=5)
+    h = pu.make_handle(w, out_dtype=0)       # bf16 out so that out shares the element strides and the buffer
+    cache = xo.OracleCache(pu.oracle_cfg(w))
+    sigma = si.key_channel_scales(w)
+    n, H, d = w.tokens_per_frame, w.n_heads, w.head_dim
+    for t in range(5):
+        q, k, v = si.frame_qkv(w, t, sigma=sigma)
+        ref = cache.step(q, k, v)
+        fused = torch.zeros((n, 4, H, d), dtype=torch.bfloat16, device="cuda:0")
+        for j, a in enumerate((q, k, v)):
+            fused[:, j] = pu.to_device(a, w)
+        h.step(fused[:, 0], fused[:, 1], fused[:, 2], fused[:, 3])
+        torch.cuda.synchronize()
+        got = fused[:, 3].float().cpu().numpy()
+        rms = float(np.sqrt((ref ** 2).mean()))
+        # bf16 store: tolerance plus half a bf16 ulp of the value itself
+        assert np.all(np.abs(got - ref) <= pu.OUT_MAX_ABS * rms + np.abs(ref) * 2.0 ** -8)
+        pu.check_state(h.export(), cache, f"strided frame {t}")
+    h.close()
+
+
+def test_two_runs_are_bit_identical():
+    import torch
+    w = _small(frames=7)
+    results = []
+    for _ in range(2):
+        h = pu.make_handle(w)
+        sigma = si.key_channel_scales(w)
+        outs = []
+        for t in range(7):
+            tq, tk, tv = (pu.to_device(a, w) for a in si.frame_qkv(w, t, sigma=sigma))
+            out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+            h.step(tq, tk, tv, out)
+            outs.append(out)
+        torch.cuda.synchronize()
+        ex = h.export()
+        results.append(([o.cpu().numpy() for o in outs], ex))
+        h.close()
+    for a, b in zip(results[0][0], results[1][0]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    for key in ("ids", "k_codes", "v_codes", "k_zero", "v_zero"):
+        assert np.array_equal(results[0][1][key], results[1][1][key])
+
+
+def test_long_stream_memory_and_length_stay_flat():
+    """1000 frames: the cache length sits at the budget, the footprint never changes, outputs stay finite."""
+    import torch
+    w = _small(tokens_per_frame=69, budget_tokens=256, n_heads=2)
+    h = pu.make_handle(w)
+    sigma = si.key_channel_scales(w)
+    ring = [tuple(pu.to_device(a, w) for a in si.frame_qkv(w, t, sigma=sigma)) for t in range(16)]
+    out = torch.empty(ring[0][0].shape, dtype=torch.float32, device="cuda:0")
+    base = None
+    for t in range(1000):
+        h.step(*ring[t % 16], out)
+        if t in (0, 3, 99, 499, 999):
+            st = h.stats()
+            base = base or st["bytes_allocated"]
+            assert st["bytes_allocated"] == base
+            assert st["cache_len_max"] == min((t + 1) * 69, 256)
+            assert bool(torch.isfinite(out).all())
+    st = h.stats()
+    assert st["frames_seen_total"] == 1000
+    assert st["tokens_dropped_total"] == 1000 * 69 - 256
+    ex = h.export()
+    assert np.array_equal(ex["ids"][:69], np.arange(69))
+    assert np.array_equal(ex["ids"][-69:], 999 * 69 + np.arange(69))
+    assert np.all(np.diff(ex["ids"]) > 0)
+    h.reset()
+    assert h.stats()["cache_len_max"] == 0
+    h.close()
+
+
+def test_step_argument_errors_leave_the_cache_untouched():
+    import torch
+    import paper_2601_01204_amd as kvx
+    w = _small()
+    h = pu.make_handle(w)
+    q, k, v = (pu.to_device(a, w) for a in si.frame_qkv(w, 0))
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(kvx.KvError) as e:
+        h.step(q, k, v, out, stream=1)
+    assert e.value.code == -3
+    with pytest.raises(kvx.KvError) as e:
+        h.step(q, k, v, out, layer=-1)
+    assert e.value.code == -3
+    with pytest.raises(kvx.KvError) as e:                     # the same cache twice in one batch
+        h.step_batched([(0, 0, q, k, v, out), (0, 0, q, k, v, out)])
+    assert e.value.code == -1
+    lib = kvx.load_library()
+    rc = lib.kv_step(h._h, 0, 0, q.data_ptr() + 2, k.data_ptr(), v.data_ptr(), q.stride(0), q.stride(1), out.data_ptr(), None)
+    assert rc == -1 and b"aligned" in lib.kv_last_error(h._h)
+    rc = lib.kv_step(h._h, 0, 0, q.data_ptr(), k.data_ptr(), v.data_ptr(), 8, 8, out.data_ptr(), None)
+    assert rc == -1
+    assert h.stats()["frames_seen_total"] == 0
+    h.step(q, k, v, out)
+    torch.cuda.synchronize()
+    assert h.stats()["frames_seen_total"] == 1
+    h.close()

@@ -66,3 +66,43 @@ def test_bf16_output_is_rounded_fp32_output():
         assert torch.equal(o32.to(torch.bfloat16), o16), f"frame {t}"
     h32.close()
     h16.close()
+
+
+def test_vggt_layer_all_frames():
+    """All 32 frames of the benchmark configuration, free-running."""
+    pu.run_stream(si.WORKLOADS["vggt_layer"], 32, check_every=8)
+
+
+def test_vggt_stack_two_layers_across_onset():
+    """Budget 16384: two layers of the 24-layer stack, batched, 18 frames (pruning starts at the 16th)."""
+    import torch
+    from oracle import xstream_oracle as xo
+    w = si.WORKLOADS["vggt_stack"]
+    layers = [0, 23]
+    h = pu.make_handle(w, n_layers=24)
+    caches = {l: xo.OracleCache(pu.oracle_cfg(w)) for l in layers}
+    sig = {l: si.key_channel_scales(w, 0, l) for l in layers}
+    for t in range(18):
+        items, chk = [], []
+        for l in layers:
+            q, k, v = si.frame_qkv(w, t, 0, l, sig[l])
+            ref = caches[l].step(q, k, v)
+            tq, tk, tv = (pu.to_device(a, w) for a in (q, k, v))
+            out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+            items.append((0, l, tq, tk, tv, out))
+            chk.append((l, out, ref))
+        h.step_batched(items)
+        torch.cuda.synchronize()
+        for l, out, ref in chk:
+            e = pu.check_output(out.cpu().numpy(), ref, f"stack layer {l} frame {t}")
+            if t >= 14:
+                pu.check_state(h.export(0, l), caches[l], f"stack layer {l} frame {t}")
+        print(f"  vggt_stack frame {t}: len {caches[0].cache_len} err {e}", flush=True)
+    h.close()
+
+
+def test_vggt_hires_int2_keys_across_onset():
+    """518x518 frames (1374 tokens), budget 24576, INT2 keys in groups of 32, INT4 values: 20 frames
+    of one stream and layer (pruning starts at the 18th)."""
+    w = si.WORKLOADS["vggt_hires"]
+    pu.run_stream(w, 20, check_every=6)
