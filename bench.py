@@ -55,6 +55,76 @@ def oracle_baseline(w, frames_total=12, steady_from=9):
                       f"{steady_from}-{frames_total - 1} (cache full at {w.budget_tokens} tokens)"}
 
 
+def aux_measurements(torch, kvx, si, dev, frames, peak_hbm):
+    """Two side measurements, outside the timed region of the headline number:
+    (1) the attention kernel alone on the benchmark workload (no second stream, all CUs);
+    (2) one batched step over the 24 independent layer caches of the 'vggt_stack' workload
+        (budget 16384), which gives the bandwidth kernels launches large enough to be judged
+        against HBM peak."""
+    out = {}
+    w = si.WORKLOADS["vggt_layer"]
+    n, H, d, L = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens
+    h = kvx.KvHandle(n_heads=H, tokens_per_frame=n, n_special=w.n_special, pool_group=w.pool_group, budget_tokens=L,
+                     k_bits=w.k_bits, k_group=w.k_group, v_bits=w.v_bits, v_group=w.v_group)
+    h.set_option("overlap_update", 0)
+    o = torch.empty((n, H, d), dtype=torch.bfloat16, device=dev)
+    for t in range(12):
+        h.step(*frames[t % len(frames)], o)
+    h.set_timing(1)
+    for t in range(50):
+        h.step(*frames[t % len(frames)], o)
+    torch.cuda.synchronize()
+    ms, cnt = h.read_timing()["attention"]
+    us = ms * 1e3 / cnt
+    out["attention_alone"] = {"us": round(us, 2), "TFLOP/s": round(4.0 * n * (L + n) * d * H / (us * 1e-6) / 1e12, 1)}
+    h.close()
+
+    w = si.WORKLOADS["vggt_stack"]
+    n, H, d, L, NL = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens, w.n_layers
+    h = kvx.KvHandle(n_layers=NL, n_heads=H, tokens_per_frame=n, n_special=w.n_special, pool_group=w.pool_group,
+                     budget_tokens=L, k_bits=w.k_bits, k_group=w.k_group, v_bits=w.v_bits, v_group=w.v_group)
+    h.set_option("overlap_update", 0)
+    outs = [torch.empty((n, H, d), dtype=torch.bfloat16, device=dev) for _ in range(NL)]
+    fill = -(-L // n) + 1
+
+    def step(t):
+        h.step_batched([(0, l, *frames[(t + l) % len(frames)], outs[l]) for l in range(NL)])
+    for t in range(fill + 2):
+        step(t)
+    torch.cuda.synchronize()
+    h.set_timing(0x7F)
+    t0 = time.perf_counter()
+    steps = 10
+    for t in range(steps):
+        step(fill + 2 + t)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tm = h.read_timing()
+    kb, vb = w.k_bits, w.v_bits
+    per_layer = {
+        "score": H * L * d * kb / 8 + H * (L // w.k_group) * d * 8 + H * L * 4,
+        "rebuild_k": 2 * (H * L * d * kb / 8 + H * (L // w.k_group) * d * 8) + n * H * d * 2,
+        "rebuild_v": 2 * (H * L * d * vb / 8 + H * L * 8) + n * H * d * 2,
+    }
+    hb = {}
+    for name, nbytes in per_layer.items():
+        ms, cnt = tm[name]
+        us = ms * 1e3 / cnt
+        gbs = NL * nbytes / (us * 1e-6) / 1e9
+        hb[name] = {"us": round(us, 2), "GB/s": round(gbs, 1), "frac": round(gbs / peak_hbm, 4)}
+    ms, cnt = tm["attention"]
+    us = ms * 1e3 / cnt
+    out["stack24_batched_step"] = {
+        "frames/s (24-layer frames)": round(steps / dt, 2),
+        "kernel_us": {k: round(v[0] * 1e3 / v[1], 2) for k, v in tm.items() if v[1]},
+        "attention_TFLOP/s": round(NL * 4.0 * n * (L + n) * d * H / (us * 1e-6) / 1e12, 1),
+        "hbm_kernels": hb,
+        "kv_bytes_live_per_layer": h.stats()["bytes_live_per_cache"],
+    }
+    h.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +133,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--splits", type=int, default=0, help="override the attention key-range split count")
     ap.add_argument("--no-overlap", action="store_true", help="run the cache update after attention instead of beside it")
+    ap.add_argument("--no-aux", action="store_true", help="skip the auxiliary measurements (standalone attention, 24-layer batched step)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 1 GiB device-to-device copies, a known-size reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -84,6 +157,14 @@ def main():
         h.set_option("attention_splits", args.splits)
     if args.no_overlap:
         h.set_option("overlap_update", 0)
+
+    if args.copy_calibration:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        c = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            a.copy_(c)
+        torch.cuda.synchronize()
+        del a, c
 
     # a ring of distinct frames, resident in HBM
     ring = w.frames
@@ -175,6 +256,9 @@ def main():
                      "bf16_uncompressed_equivalent": 2 * H * L * d * 2},
     }
     h.close()
+
+    if not args.no_aux:
+        res["aux"] = aux_measurements(torch, kvx, si, dev, frames, PEAK_HBM_GBS)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = oracle_baseline(w)
     else:
