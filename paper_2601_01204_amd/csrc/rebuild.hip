@@ -24,6 +24,39 @@ __device__ __forceinline__ int quant_code(float x, float s, int32_t z, int level
   return min(max(q, 0), levels);
 }
 
+// x / s for many x and one s.  The correctly rounded fp32 quotient is what the compiler's
+// own expansion of `/` computes as a reciprocal refined by one Newton step followed by two
+// fused residual corrections of the quotient; that expansion also rescales operands with
+// extreme exponents.  With the refined reciprocal computed once per scale and s in a range
+// where no rescaling happens, the five fused operations below are that expansion's core and
+// give the same bits.  Scales outside the range take the plain division.
+struct Divider {
+  float s, r;
+  bool safe;
+};
+__device__ __forceinline__ Divider make_divider(float s) {
+  Divider d;
+  d.s = s;
+  const float r0 = __builtin_amdgcn_rcpf(s);
+  const float e0 = __builtin_fmaf(-s, r0, 1.0f);
+  d.r = __builtin_fmaf(e0, r0, r0);
+  const float a = fabsf(s);
+  d.safe = a > 0x1p-60f && a < 0x1p60f;
+  return d;
+}
+__device__ __forceinline__ float div_by(float x, const Divider& d) {
+  if (!d.safe || !(fabsf(x) < 0x1p60f)) return x / d.s;
+  const float q0 = x * d.r;
+  const float e1 = __builtin_fmaf(-d.s, q0, x);
+  const float q1 = __builtin_fmaf(e1, d.r, q0);
+  const float e2 = __builtin_fmaf(-d.s, q1, x);
+  return __builtin_fmaf(e2, d.r, q1);
+}
+__device__ __forceinline__ int quant_code_div(float x, const Divider& d, int32_t z, int levels) {
+  const int q = (int)rintf(div_by(x, d)) + z;
+  return min(max(q, 0), levels);
+}
+
 // 16 consecutive channels of one row as fp32, from a quantised row (with that row's group
 // metadata) or from an input row.
 template <int B>
@@ -120,10 +153,10 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
   const int grp = p / g.k_group;
   const bool carried = grp < g0;
 
-  __shared__ float vals[kTileK][kHeadDim + 1];
+  __shared__ __attribute__((aligned(16))) float vals[kTileK][kHeadDim + 4];
   __shared__ float pmin[4][kHeadDim], pmax[4][kHeadDim];
-  __shared__ float gs[2][kHeadDim];
-  __shared__ int32_t gz[2][kHeadDim];
+  __shared__ __attribute__((aligned(16))) float gs[2][kHeadDim];
+  __shared__ __attribute__((aligned(16))) int32_t gz[2][kHeadDim];
 
   float x[16];
   uint32_t wsrc[4] = {0, 0, 0, 0};
@@ -136,17 +169,25 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
       if (!carried) {
         const int sg = src / g.k_group;
         const int64_t moff = ((int64_t)h * g.g_cap + sg) * kHeadDim + cb * 16;
-        const float* sp = reinterpret_cast<const float*>(cur + g.lay.k_scale) + moff;
-        const int32_t* zp = reinterpret_cast<const int32_t*>(cur + g.lay.k_zero) + moff;
+        const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(cur + g.lay.k_scale) + moff);
+        const int4* zp = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(cur + g.lay.k_zero) + moff);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) x[e] = sp[e] * (float)(code16<B>(wsrc, e) - zp[e]);
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const float4 sv = sp[v4];
+          const int4 zv = zp[v4];
+          x[4 * v4 + 0] = sv.x * (float)(code16<B>(wsrc, 4 * v4 + 0) - zv.x);
+          x[4 * v4 + 1] = sv.y * (float)(code16<B>(wsrc, 4 * v4 + 1) - zv.y);
+          x[4 * v4 + 2] = sv.z * (float)(code16<B>(wsrc, 4 * v4 + 2) - zv.z);
+          x[4 * v4 + 3] = sv.w * (float)(code16<B>(wsrc, 4 * v4 + 3) - zv.w);
+        }
       }
     } else {
       load_input16(it.k, (int64_t)(src - t_c) * g.tok_stride + (int64_t)h * g.head_stride + cb * 16, g.in_f32, x);
     }
   }
 #pragma unroll
-  for (int e = 0; e < 16; ++e) vals[r][cb * 16 + e] = x[e];
+  for (int v4 = 0; v4 < 4; ++v4)
+    *reinterpret_cast<float4*>(&vals[r][cb * 16 + 4 * v4]) = make_float4(x[4 * v4], x[4 * v4 + 1], x[4 * v4 + 2], x[4 * v4 + 3]);
   __syncthreads();
 
   // per-channel min / max over each quarter of the rows
@@ -205,7 +246,14 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
       const int gi = r / g.k_group;
       int code[16];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) code[e] = quant_code(x[e], gs[gi][cb * 16 + e], gz[gi][cb * 16 + e], levels);
+      for (int v4 = 0; v4 < 4; ++v4) {
+        const float4 sv = *reinterpret_cast<const float4*>(&gs[gi][cb * 16 + 4 * v4]);
+        const int4 zv = *reinterpret_cast<const int4*>(&gz[gi][cb * 16 + 4 * v4]);
+        code[4 * v4 + 0] = quant_code_div(x[4 * v4 + 0], make_divider(sv.x), zv.x, levels);
+        code[4 * v4 + 1] = quant_code_div(x[4 * v4 + 1], make_divider(sv.y), zv.y, levels);
+        code[4 * v4 + 2] = quant_code_div(x[4 * v4 + 2], make_divider(sv.z), zv.z, levels);
+        code[4 * v4 + 3] = quant_code_div(x[4 * v4 + 3], make_divider(sv.w), zv.w, levels);
+      }
       pack16<B>(code, dst);
     }
   }
@@ -262,8 +310,9 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b) {
     int32_t z;
     quant_params(mn, mx, levels, s, z);
     int code[16];
+    const Divider dv = make_divider(s);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) code[e] = quant_code(x[e], s, z, levels);
+    for (int e = 0; e < 16; ++e) code[e] = quant_code_div(x[e], dv, z, levels);
     pack16<B>(code, dst);
     if ((cb % lanes_per_group) == 0) {
       VMeta m;
