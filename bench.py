@@ -23,11 +23,11 @@ if ROOT not in sys.path:
 PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
-# profiles/attention_vggt_layer_pmc.txt); None until measured.
-ATTENTION_TRAFFIC_BYTES = None
+# profiles/attn_kernel_vggt_layer_counters.txt), fetch counter scaled by 2.00, write by 1.00.
+ATTENTION_TRAFFIC_BYTES = 38.65e6
 
 
-def oracle_baseline(w, frames_total=12, steady_from=9):
+def oracle_baseline(w, frames_total=18, steady_from=9):
     """The CPU oracle as it stands, timed on this host: frames 0..frames_total-1 of the same
     stream; the rate is taken over the steady frames (cache full, pruning every step)."""
     import numpy as np
