@@ -328,7 +328,7 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
         launch_score(b, max_tc, sb);
         record(h, KV_K_SCORE, false, sb);
         record(h, KV_K_SELECT, true, sb);
-        launch_select(b, sb);
+        launch_select(b, max_tc, sb);
         record(h, KV_K_SELECT, false, sb);
       }
       record(h, KV_K_REBUILD_K, true, sb);

@@ -106,7 +106,7 @@ void launch_attention(const KvxBatch& b, int max_tiles, hipStream_t st);
 void launch_combine(const KvxBatch& b, hipStream_t st);
 void launch_pool(const KvxBatch& b, hipStream_t st);
 void launch_score(const KvxBatch& b, int max_tc, hipStream_t st);
-void launch_select(const KvxBatch& b, hipStream_t st);
+void launch_select(const KvxBatch& b, int max_tc, hipStream_t st);
 void launch_rebuild_k(const KvxBatch& b, int max_tnew, hipStream_t st);
 void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st);
 void launch_append_bf16(const KvxBatch& b, hipStream_t st);

@@ -45,18 +45,45 @@ __device__ __forceinline__ int block_scan_excl(int v, int* wave_sums, int& total
   return base + inc - v;
 }
 
+// S_j = (D[0,j] + D[1,j] + ... + D[H-1,j]) / H for the middle tokens, heads added in order
+// (Eq. 4-6), and the order-preserving key of each score.  One thread per token, the H
+// loads of a token independent of each other.
+__global__ __launch_bounds__(256) void score_sum_kernel(const KvxBatch b) {
+  const Geometry& g = b.g;
+  const Item it = b.items[blockIdx.y];
+  if (!it.prune) return;
+  const int n = g.n, H = g.H;
+  const int M = it.t_c - n;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= M) return;
+  uint8_t* sc = cache_scratch(g, it.cache);
+  const float* d0 = reinterpret_cast<const float*>(sc + g.sl.dots) + n + i;
+  float acc = d0[0];
+  int h = 1;
+  for (; h + 7 < H; h += 8) {
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = d0[(int64_t)(h + k) * g.t_cap];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc = acc + v[k];
+  }
+  for (; h < H; ++h) acc = acc + d0[(int64_t)h * g.t_cap];
+  const float s = acc / (float)H;
+  reinterpret_cast<float*>(sc + g.sl.scores)[i] = s;
+  reinterpret_cast<uint32_t*>(sc + g.sl.keys)[i] = order_key(s);
+}
+
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.x];
   if (!it.prune) return;
-  const int n = g.n, t_c = it.t_c, H = g.H;
+  const int n = g.n, t_c = it.t_c;
   const int M = t_c - n;                 // middle tokens: cache positions n .. t_c - 1
   const int T = t_c + n;
   const int n_drop = T - g.budget;       // >= 1
   const int k_keep = M - n_drop;         // = budget - 2n
   uint8_t* sc = cache_scratch(g, it.cache);
-  const float* dots = reinterpret_cast<const float*>(sc + g.sl.dots);
-  float* scores = reinterpret_cast<float*>(sc + g.sl.scores);
+  const uint32_t* keys = reinterpret_cast<const uint32_t*>(sc + g.sl.keys);
   int32_t* keep = reinterpret_cast<int32_t*>(sc + g.sl.keep);
   int32_t* sel = reinterpret_cast<int32_t*>(sc + g.sl.sel);
   const int tid = threadIdx.x;
@@ -69,29 +96,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   __shared__ int sh_eq;
   __shared__ uint8_t flags[kSelMaxM];
 
-  // S_j = (D[0,j] + D[1,j] + ... + D[H-1,j]) / H, heads added in order (Eq. 4-6).
   uint32_t key[kSelPerThread];
 #pragma unroll
   for (int k = 0; k < kSelPerThread; ++k) {
     const int i = tid + k * kSelThreads;
-    key[k] = 0u;
-    if (i < M) {
-      const float* d0 = dots + n + i;
-      float acc = d0[0];
-      int h = 1;
-      for (; h + 3 < H; h += 4) {      // loads of four heads in flight, additions in head order
-        const float a = d0[(int64_t)h * g.t_cap], c = d0[(int64_t)(h + 1) * g.t_cap];
-        const float e = d0[(int64_t)(h + 2) * g.t_cap], f = d0[(int64_t)(h + 3) * g.t_cap];
-        acc = acc + a;
-        acc = acc + c;
-        acc = acc + e;
-        acc = acc + f;
-      }
-      for (; h < H; ++h) acc = acc + d0[(int64_t)h * g.t_cap];
-      const float s = acc / (float)H;
-      scores[i] = s;
-      key[k] = order_key(s);
-    }
+    key[k] = i < M ? keys[i] : 0u;
   }
   if (tid == 0) {
     sh_prefix = 0u;
@@ -182,7 +191,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   }
 }
 
-void launch_select(const KvxBatch& b, hipStream_t st) {
+void launch_select(const KvxBatch& b, int max_tc, hipStream_t st) {
+  hipLaunchKernelGGL(score_sum_kernel, dim3((max_tc + 255) / 256, b.n_items), dim3(256), 0, st, b);
   hipLaunchKernelGGL(select_kernel, dim3(b.n_items), dim3(kSelThreads), 0, st, b);
 }
 
