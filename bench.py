@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the compressed-KV streaming attention step on one MI355X.
 
-A step is one kv_step() on the 'vggt_layer' workload (benchmark configs[1]: one
+A step is one kv_step() on the 'vggt_layer' workload (the benchmark's second configuration: one
 VGGT-scale global-attention layer, 16 heads x 64, 1041 tokens per frame, budget 8192,
 INT4 keys per channel / INT4 values per token, group 64) in steady state, i.e. with the
 cache full so that every step attends over 8192 + 1041 keys, scores, prunes 1041 tokens

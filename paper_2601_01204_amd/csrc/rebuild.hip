@@ -52,6 +52,14 @@ __device__ __forceinline__ float div_by(float x, const Divider& d) {
   const float e2 = __builtin_fmaf(-d.s, q1, x);
   return __builtin_fmaf(e2, d.r, q1);
 }
+// The five fused operations alone, for a scale already known to be in the safe range.
+__device__ __forceinline__ float div_fast(float x, float s, float r) {
+  const float q0 = x * r;
+  const float e1 = __builtin_fmaf(-s, q0, x);
+  const float q1 = __builtin_fmaf(e1, r, q0);
+  const float e2 = __builtin_fmaf(-s, q1, x);
+  return __builtin_fmaf(e2, r, q1);
+}
 __device__ __forceinline__ int quant_code_div(float x, const Divider& d, int32_t z, int levels) {
   const int q = (int)rintf(div_by(x, d)) + z;
   return min(max(q, 0), levels);
@@ -129,7 +137,7 @@ __device__ __forceinline__ void load_input16(const void* base, int64_t off, int 
 // from the fp32 values of its members: de-quantised codes for surviving tokens, input
 // values for the new frame.
 template <int B>
-__global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
+__global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
@@ -156,7 +164,9 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
   __shared__ __attribute__((aligned(16))) float vals[kTileK][kHeadDim + 4];
   __shared__ float pmin[4][kHeadDim], pmax[4][kHeadDim];
   __shared__ __attribute__((aligned(16))) float gs[2][kHeadDim];
+  __shared__ __attribute__((aligned(16))) float gr[2][kHeadDim];     // refined reciprocals of the scales
   __shared__ __attribute__((aligned(16))) int32_t gz[2][kHeadDim];
+  __shared__ int unsafe_scales;                                      // some scale needs the plain division
 
   float x[16];
   uint32_t wsrc[4] = {0, 0, 0, 0};
@@ -190,6 +200,7 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
     *reinterpret_cast<float4*>(&vals[r][cb * 16 + 4 * v4]) = make_float4(x[4 * v4], x[4 * v4 + 1], x[4 * v4 + 2], x[4 * v4 + 3]);
   __syncthreads();
 
+  if (tid == 0) unsafe_scales = 0;
   // per-channel min / max over each quarter of the rows
   {
     const int c = tid & 63, qtr = tid >> 6;
@@ -228,8 +239,11 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
         quant_params(mn, mx, levels, s, z);
         if (h == 0 && c == 0) atomicAdd(&sel[2], 1);
       }
+      const Divider dv = make_divider(s);
       gs[gi][c] = s;
+      gr[gi][c] = dv.r;
       gz[gi][c] = z;
+      if (!dv.safe) unsafe_scales = 1;
       reinterpret_cast<float*>(nxt + g.lay.k_scale)[moff] = s;
       reinterpret_cast<int32_t*>(nxt + g.lay.k_zero)[moff] = z;
     }
@@ -245,14 +259,23 @@ __global__ __launch_bounds__(256) void rebuild_k_kernel(const KvxBatch b) {
     } else {
       const int gi = r / g.k_group;
       int code[16];
+      if (unsafe_scales) {                      // block-uniform and rare
 #pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        const float4 sv = *reinterpret_cast<const float4*>(&gs[gi][cb * 16 + 4 * v4]);
-        const int4 zv = *reinterpret_cast<const int4*>(&gz[gi][cb * 16 + 4 * v4]);
-        code[4 * v4 + 0] = quant_code_div(x[4 * v4 + 0], make_divider(sv.x), zv.x, levels);
-        code[4 * v4 + 1] = quant_code_div(x[4 * v4 + 1], make_divider(sv.y), zv.y, levels);
-        code[4 * v4 + 2] = quant_code_div(x[4 * v4 + 2], make_divider(sv.z), zv.z, levels);
-        code[4 * v4 + 3] = quant_code_div(x[4 * v4 + 3], make_divider(sv.w), zv.w, levels);
+        for (int e = 0; e < 16; ++e) code[e] = quant_code(x[e], gs[gi][cb * 16 + e], gz[gi][cb * 16 + e], levels);
+      } else {
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const float4 sv = *reinterpret_cast<const float4*>(&gs[gi][cb * 16 + 4 * v4]);
+          const float4 rv = *reinterpret_cast<const float4*>(&gr[gi][cb * 16 + 4 * v4]);
+          const int4 zv = *reinterpret_cast<const int4*>(&gz[gi][cb * 16 + 4 * v4]);
+          const float sa[4] = {sv.x, sv.y, sv.z, sv.w}, ra[4] = {rv.x, rv.y, rv.z, rv.w};
+          const int za[4] = {zv.x, zv.y, zv.z, zv.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int q = (int)rintf(div_fast(x[4 * v4 + k], sa[k], ra[k])) + za[k];
+            code[4 * v4 + k] = min(max(q, 0), levels);
+          }
+        }
       }
       pack16<B>(code, dst);
     }
