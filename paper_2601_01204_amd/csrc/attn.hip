@@ -20,9 +20,11 @@
 // split the same way (queries too).
 //
 // Softmax.  The softmax scale times log2(e) is folded into the keys as they are staged,
-// so S^T is already in log2 units.  Each query keeps a reference m that is raised only
-// when a key exceeds it by more than kRescaleGap (then O and l are rescaled, a rare,
-// wave-uniform branch); otherwise p = 2^(s - m) <= 2^kRescaleGap needs no rescale.
+// so S^T is already in log2 units.  Each query keeps a reference m and p = 2^(s - m) is
+// formed without looking at the tile's maximum first: f16 holds p up to 2^16, and a key
+// further above m than that makes p, and so the row sum, infinite.  Only then (a rare,
+// wave-uniform branch) is m raised for every row whose largest key exceeds it by more
+// than kRescaleGap, O and l are rescaled and the tile's probabilities are formed again.
 //
 // Schedule.  Measured on gfx950, an MFMA overlaps only one or two vector instructions of
 // its own wave but ~20 of its 32 cycles with vector work of the other wave on the SIMD.
@@ -46,6 +48,7 @@ constexpr int kLdsRow = 72;                       // 16-bit elements per LDS row
 constexpr int kTileElems = kTileK * kLdsRow;      // one K or V^T tile
 constexpr float kNegBig = -1.0e30f;
 constexpr float kRescaleGap = 8.0f;               // log2 units
+constexpr float kSumLimit = 1.0e37f;              // a row sum at or above this (or NaN) saw an f16 overflow
 
 #define KVX_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -380,21 +383,44 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
           }
         }
     }
-    // raise the references where a key exceeds them by more than the gap (rare)
-    float mx[2];
-    bool need = false;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      float a = fmaxf(s[0][nb][0], s[1][nb][0]);
-#pragma unroll
-      for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s[0][nb][r]), s[1][nb][r]);
-      mx[nb] = a;
-      need |= a > m_ref[nb] + kRescaleGap;
-    }
-    if (__any(need)) {
+    // p = 2^(s - m), packed to f16 as the B operand of the second product, summed into l.
+    // The reference m is not checked beforehand: a key that exceeds it by more than the
+    // f16 range allows turns its p, and with it the row sum, into infinity; only then
+    // (rare, wave-uniform) are the references raised and the probabilities recomputed.
+    f16x8 pb[2][4];                   // [query block][16-key step]
+    float l_new[2];
+    auto probabilities = [&]() __attribute__((always_inline)) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const float mq = fmaxf(mx[nb], __shfl_xor(mx[nb], 32));      // both halves of a query agree
+        float l = l_run[nb];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const int mb = kk >> 1, r0 = (kk & 1) * 8;
+          uint32_t w[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p0 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e] - m_ref[nb]);
+            const float p1 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e + 1] - m_ref[nb]);
+            w[e] = pack_f16(p0, p1);
+            l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w[e]), ones, l, false);
+          }
+          pb[nb][kk] = __builtin_bit_cast(f16x8, make_uint4(w[0], w[1], w[2], w[3]));
+        }
+        l_new[nb] = l;
+      }
+    };
+    probabilities();
+    bool overflow = false;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) overflow |= !(l_new[nb] < kSumLimit);
+    if (__any(overflow)) {
+      // raise the references of the rows whose largest key exceeds them by more than the gap
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        float a = fmaxf(s[0][nb][0], s[1][nb][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s[0][nb][r]), s[1][nb][r]);
+        const float mq = fmaxf(a, __shfl_xor(a, 32));                // both halves of a query agree
         const float m_new = (mq > m_ref[nb] + kRescaleGap) ? mq : m_ref[nb];
         const float alpha = __builtin_amdgcn_exp2f(m_ref[nb] - m_new);
         m_ref[nb] = m_new;
@@ -404,25 +430,10 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[cb][nb][r] *= alpha;
       }
+      probabilities();
     }
-    // p = 2^(s - m), packed to f16 as the B operand of the second product, summed into l
-    f16x8 pb[2][4];                   // [query block][16-key step]
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int mb = kk >> 1, r0 = (kk & 1) * 8;
-        uint32_t w[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p0 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e] - m_ref[nb]);
-          const float p1 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e + 1] - m_ref[nb]);
-          w[e] = pack_f16(p0, p1);
-          l_run[nb] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w[e]), ones, l_run[nb], false);
-        }
-        pb[nb][kk] = __builtin_bit_cast(f16x8, make_uint4(w[0], w[1], w[2], w[3]));
-      }
-    }
+    for (int nb = 0; nb < NB; ++nb) l_run[nb] = l_new[nb];
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
