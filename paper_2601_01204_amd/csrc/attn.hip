@@ -73,38 +73,33 @@ __device__ __forceinline__ void split_bf16(float a, float b, uint32_t& hi, uint3
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-template <int B>
-__device__ __forceinline__ int code_at(const uint32_t (&w)[2], int e) {
-  if constexpr (B == 4) return (int)((w[0] >> (4 * e)) & 0xFu);
-  if constexpr (B == 2) return (int)((w[0] >> (2 * e)) & 0x3u);
-  return (int)((w[e >> 2] >> (8 * (e & 3))) & 0xFFu);
-}
+// The codes of eight consecutive channels of one row: 2, 4 or 8 bytes.
+template <int B> struct Octet;
+template <> struct Octet<2> { typedef uint16_t type; };
+template <> struct Octet<4> { typedef uint32_t type; };
+template <> struct Octet<8> { typedef uint2 type; };
 
 template <int B>
-__device__ __forceinline__ void load_octet(const uint8_t* p, uint32_t (&w)[2]) {
-  if constexpr (B == 4) {
-    w[0] = *reinterpret_cast<const uint32_t*>(p);
-    w[1] = 0;
-  } else if constexpr (B == 2) {
-    w[0] = *reinterpret_cast<const uint16_t*>(p);
-    w[1] = 0;
-  } else {
-    const uint2 t = *reinterpret_cast<const uint2*>(p);
-    w[0] = t.x;
-    w[1] = t.y;
-  }
+__device__ __forceinline__ int octet_code(const typename Octet<B>::type& w, int e) {
+  if constexpr (B == 4) return (int)((w >> (4 * e)) & 0xFu);
+  else if constexpr (B == 2) return (int)(((uint32_t)w >> (2 * e)) & 0x3u);
+  else return (int)(((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xFFu);
 }
 
-template <bool F32IN>
+// Staging registers of one thread: two rows x eight channels of K (waves 0-3) or of V
+// (waves 4-7) as loaded, before decoding.  Every tile fills the same registers with the
+// same straight-line sequence of loads, whatever the tile holds (only the addresses are
+// selected), so the loads of a later tile stay in flight across the barriers.
+//   cached K tile : c = the two rows' codes, a[0..1] = the channels' scales, a[2..3] = zero-points
+//   cached V tile : c = codes, m = the two rows' (scale, zero-point)
+//   bf16 rows     : a[0], a[1] = the two rows (own frame, uncompressed cache)
+//   fp32 rows     : a[0..1] = first row, a[2..3] = second row (own frame)
+// Registers a tile does not use are loaded from a valid dummy address.
+template <int B>
 struct TileRaw {
-  // Staging registers of one thread: two rows x eight channels of K (waves 0-3) or of V
-  // (waves 4-7).  Cache tile: codes plus metadata (K: the eight channels' scale and
-  // zero-point; V: the two rows' scale and zero-point in s[0..1], z[0..1]).
-  uint32_t c[2][2];
-  float s[8];
-  int32_t z[8];
-  uint4 row[2];                         // bf16 rows (own frame, uncompressed cache)
-  float row32[F32IN ? 2 : 1][8];        // fp32 rows (own frame)
+  uint4 a[4];
+  typename Octet<B>::type c[2];
+  uint2 m[2];
 };
 
 __device__ __forceinline__ void load8_f32(const void* base, int64_t off, float (&x)[8]) {
@@ -133,6 +128,7 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_khi[2][kTileElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_klo[2][kTileElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileElems];
+  __shared__ uint4 lds_q[8 * 2 * 4 * 64];                 // 8 waves x 2 sets x 4 channel steps x 64 lanes
 
   const int n = g.n;
   const int t_c = it.t_c;
@@ -154,14 +150,16 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   int nblk = blk_base + (wave < blk_extra ? 1 : 0);
   if (row0 + 32 >= n) nblk = min(nblk, 1);
   if (row0 >= n) nblk = 0;                        // such a wave only helps with staging
-  const bool stage_first = wave >= 4;      // waves 4-7 stage the next tile before computing
   const bool role_k = wave < 4;            // waves 0-3 stage K, waves 4-7 stage V
 
   // ---- this wave's query fragments (B operand of S^T = K Q^T) ---------------------
-  bf16x8 qf[2][4];
-  bf16x8 qlo[F32IN ? 2 : 1][4];
+  // They live in a private LDS region of the wave, one 16-byte entry per lane, fragment
+  // and 16-channel step, and are re-read every tile: the registers they would occupy hold
+  // the -m blocks below instead.  bf16 input: set = query block.  fp32 input (one query
+  // block per wave): set 0 = hi, set 1 = lo part.
+  uint4* qbase = lds_q + (wave * 2 * 4) * 64 + lane;
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
+  for (int nb = 0; nb < (F32IN ? 1 : 2); ++nb) {
     const int qi = (nb < nblk) ? row0 + nb * 32 + l32 : n;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -172,22 +170,28 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) split_bf16(x[2 * e], x[2 * e + 1], hi[e], lo[e]);
-        qf[nb][ks] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
-        qlo[nb][ks] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+        qbase[(0 * 4 + ks) * 64] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        qbase[(1 * 4 + ks) * 64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
       } else {
         uint4 v = make_uint4(0, 0, 0, 0);
         if (qi < n) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.q) + off);
-        qf[nb][ks] = __builtin_bit_cast(bf16x8, v);
+        qbase[(nb * 4 + ks) * 64] = v;
       }
     }
   }
 
   f32x16 o[2][2];                     // [channel block][query block]
-  float m_ref[2], l_run[2];           // per query block; lanes l and l + 32 hold the same m_ref
+  // Per query block: the reference m (lanes l and l + 32 hold the same value), the running
+  // row sum, and a 16-register block filled with -m that the first MFMA of every tile
+  // takes as its accumulator input, so S^T leaves the matrix core as s - m.
+  f32x16 negm[2];
+  float m_ref[2], l_run[2];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    m_ref[nb] = kNegBig;
+    m_ref[nb] = 0.f;
     l_run[nb] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[nb][r] = 0.f;
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -203,57 +207,71 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   constexpr int kVRow = 8 * VB;
   const int ngv = kHeadDim / g.v_group;
 
-  TileRaw<F32IN> raw;
+  const int k_shift = g.k_group == 64 ? 6 : 5;
+  const int v_shift = g.v_group == 64 ? 6 : 5;
 
-  auto load_raw = [&](int tile) __attribute__((always_inline)) {
+  // Addresses of tile `tile`'s raw data for this thread, then the loads.  `tile` may be any
+  // tile of the range (a tile past the end is clamped by the caller and simply not decoded).
+  auto load_raw = [&](auto rolec, auto& raw, int tile) __attribute__((always_inline)) {
+    constexpr bool ROLE_K = decltype(rolec)::value;
+    constexpr int B = ROLE_K ? KB : VB;
+    typedef typename Octet<B>::type CodeT;
+    const uint8_t *pa0, *pa1, *pa2, *pa3, *pc0, *pc1, *pm0, *pm1;
     if (tile < ntc && compressed) {
       const int ja = tile * kTileK + key_a;
-      if (role_k) {
-        const uint8_t* kcp = half + g.lay.k_codes + ((int64_t)h * g.t_cap + ja) * kKRow + co * KB;
-        load_octet<KB>(kcp, raw.c[0]);
-        load_octet<KB>(kcp + kKRow, raw.c[1]);
-        const int grp = ja / g.k_group;
-        const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + co * 8;
-        const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(half + g.lay.k_scale) + moff);
-        const int4* zp = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(half + g.lay.k_zero) + moff);
-        const float4 s0 = sp[0], s1 = sp[1];
-        const int4 z0 = zp[0], z1 = zp[1];
-        raw.s[0] = s0.x; raw.s[1] = s0.y; raw.s[2] = s0.z; raw.s[3] = s0.w;
-        raw.s[4] = s1.x; raw.s[5] = s1.y; raw.s[6] = s1.z; raw.s[7] = s1.w;
-        raw.z[0] = z0.x; raw.z[1] = z0.y; raw.z[2] = z0.z; raw.z[3] = z0.w;
-        raw.z[4] = z1.x; raw.z[5] = z1.y; raw.z[6] = z1.z; raw.z[7] = z1.w;
+      const int64_t row = (int64_t)h * g.t_cap + ja;
+      if constexpr (ROLE_K) {
+        pc0 = half + g.lay.k_codes + row * kKRow + co * KB;
+        pc1 = pc0 + kKRow;
+        const int64_t moff = (((int64_t)h * g.g_cap + (ja >> k_shift)) * kHeadDim + co * 8) * 4;
+        pa0 = half + g.lay.k_scale + moff;
+        pa1 = pa0 + 16;
+        pa2 = half + g.lay.k_zero + moff;
+        pa3 = pa2 + 16;
+        pm0 = pm1 = pa0;
       } else {
-        const uint8_t* vcp = half + g.lay.v_codes + ((int64_t)h * g.t_cap + ja) * kVRow + co * VB;
-        load_octet<VB>(vcp, raw.c[0]);
-        load_octet<VB>(vcp + kVRow, raw.c[1]);
-        const VMeta* vmp = reinterpret_cast<const VMeta*>(half + g.lay.v_meta) + ((int64_t)h * g.t_cap + ja) * ngv + (co * 8) / g.v_group;
-        const VMeta m0 = vmp[0], m1 = vmp[ngv];
-        raw.s[0] = m0.s; raw.z[0] = m0.z;
-        raw.s[1] = m1.s; raw.z[1] = m1.z;
+        const uint8_t* rowp = half + g.lay.v_codes + row * kVRow;
+        pc0 = rowp + co * VB;
+        pc1 = pc0 + kVRow;
+        pm0 = half + g.lay.v_meta + (row * ngv + ((co * 8) >> v_shift)) * (int64_t)sizeof(VMeta);
+        pm1 = pm0 + ngv * (int)sizeof(VMeta);
+        pa0 = pa1 = pa2 = pa3 = rowp;
       }
-    } else if (tile < ntc) {
-      // uncompressed bf16 cache: rows of 64 bf16
-      const int ja = tile * kTileK + key_a;
-      const uint16_t* src = reinterpret_cast<const uint16_t*>(half + (role_k ? g.lay.k_codes : g.lay.v_codes)) +
-                            ((int64_t)h * g.t_cap + ja) * kHeadDim + co * 8;
-      raw.row[0] = *reinterpret_cast<const uint4*>(src);
-      raw.row[1] = *reinterpret_cast<const uint4*>(src + kHeadDim);
     } else {
-      const int ia = (tile - ntc) * kTileK + key_a;
-      const void* src = role_k ? it.k : it.v;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const bool ok = (ia + i) < n;
-        const int64_t off = (int64_t)(ia + i) * g.tok_stride + (int64_t)h * g.head_stride + co * 8;
+      if (tile < ntc) {
+        // uncompressed bf16 cache: rows of 64 bf16; the row after a tile's last valid one is in bounds
+        const int ja = tile * kTileK + key_a;
+        pa0 = half + (ROLE_K ? g.lay.k_codes : g.lay.v_codes) + (((int64_t)h * g.t_cap + ja) * kHeadDim + co * 8) * 2;
+        pa1 = pa0 + kHeadDim * 2;
+        pa2 = pa3 = pa0;
+      } else {
+        const int ia = (tile - ntc) * kTileK + key_a;
+        const int i0 = min(ia, n - 1), i1 = min(ia + 1, n - 1);      // rows past the frame are zeroed when decoded
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(ROLE_K ? it.k : it.v);
+        const int64_t o0 = (int64_t)i0 * g.tok_stride + (int64_t)h * g.head_stride + co * 8;
+        const int64_t o1 = (int64_t)i1 * g.tok_stride + (int64_t)h * g.head_stride + co * 8;
         if constexpr (F32IN) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) raw.row32[i][e] = 0.f;
-          if (ok) load8_f32(src, off, raw.row32[i]);
+          pa0 = src + o0 * 4; pa1 = pa0 + 16;
+          pa2 = src + o1 * 4; pa3 = pa2 + 16;
         } else {
-          raw.row[i] = make_uint4(0, 0, 0, 0);
-          if (ok) raw.row[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(src) + off);
+          pa0 = src + o0 * 2;
+          pa1 = src + o1 * 2;
+          pa2 = pa3 = pa0;
         }
       }
+      pc0 = pc1 = pm0 = pm1 = pa0;
+    }
+    raw.c[0] = *reinterpret_cast<const CodeT*>(pc0);
+    raw.c[1] = *reinterpret_cast<const CodeT*>(pc1);
+    raw.a[0] = *reinterpret_cast<const uint4*>(pa0);
+    raw.a[1] = *reinterpret_cast<const uint4*>(pa1);
+    if constexpr (ROLE_K || F32IN) {
+      raw.a[2] = *reinterpret_cast<const uint4*>(pa2);
+      raw.a[3] = *reinterpret_cast<const uint4*>(pa3);
+    }
+    if constexpr (!ROLE_K) {
+      raw.m[0] = *reinterpret_cast<const uint2*>(pm0);
+      raw.m[1] = *reinterpret_cast<const uint2*>(pm1);
     }
   };
 
@@ -273,19 +291,22 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   };
 
   // De-quantise / convert the raw registers of `tile` into LDS buffer `buf`.
-  auto decode_store = [&](int tile, int buf, int vbuf) __attribute__((always_inline)) {
+  auto decode_store = [&](auto rolec, const auto& raw, int tile, int buf) __attribute__((always_inline)) {
+    constexpr bool ROLE_K = decltype(rolec)::value;
     if (tile < ntc && compressed) {
       const int ja = tile * kTileK + key_a;
       const bool full = (tile + 1) * kTileK <= t_c;
-      if (role_k) {
+      if constexpr (ROLE_K) {
+        const uint32_t sw[8] = {raw.a[0].x, raw.a[0].y, raw.a[0].z, raw.a[0].w, raw.a[1].x, raw.a[1].y, raw.a[1].z, raw.a[1].w};
+        const uint32_t zw[8] = {raw.a[2].x, raw.a[2].y, raw.a[2].z, raw.a[2].w, raw.a[3].x, raw.a[3].y, raw.a[3].z, raw.a[3].w};
         float sk[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sk[e] = raw.s[e] * sc;
+        for (int e = 0; e < 8; ++e) sk[e] = __uint_as_float(sw[e]) * sc;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
           float x[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) x[e] = sk[e] * (float)(code_at<KB>(raw.c[i], e) - raw.z[e]);
+          for (int e = 0; e < 8; ++e) x[e] = sk[e] * (float)(octet_code<KB>(raw.c[i], e) - (int32_t)zw[e]);
           if (!full && (ja + i) >= t_c) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] = 0.f;
@@ -293,11 +314,13 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
           store_k_split(buf, i, x);
         }
       } else {
+        const float s0 = __uint_as_float(raw.m[0].x), s1 = __uint_as_float(raw.m[1].x);
+        const int32_t z0 = (int32_t)raw.m[0].y, z1 = (int32_t)raw.m[1].y;
         float va[8], vb[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          va[e] = raw.s[0] * (float)(code_at<VB>(raw.c[0], e) - raw.z[0]);
-          vb[e] = raw.s[1] * (float)(code_at<VB>(raw.c[1], e) - raw.z[1]);
+          va[e] = s0 * (float)(octet_code<VB>(raw.c[0], e) - z0);
+          vb[e] = s1 * (float)(octet_code<VB>(raw.c[1], e) - z1);
         }
         if (!full) {
 #pragma unroll
@@ -306,21 +329,27 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
             if (ja + 1 >= t_c) vb[e] = 0.f;
           }
         }
-        store_v_pair(vbuf, va, vb);
+        store_v_pair(buf, va, vb);
       }
     } else {
       int base_row, limit;
       if (tile < ntc) { base_row = tile * kTileK; limit = t_c; } else { base_row = (tile - ntc) * kTileK; limit = n; }
+      const bool ok0 = base_row + key_a < limit, ok1 = base_row + key_a + 1 < limit;
       float x0[8], x1[8];
       if (F32IN && tile >= ntc) {
         if constexpr (F32IN) {
+          const uint32_t r0[8] = {raw.a[0].x, raw.a[0].y, raw.a[0].z, raw.a[0].w, raw.a[1].x, raw.a[1].y, raw.a[1].z, raw.a[1].w};
+          const uint32_t r1[8] = {raw.a[2].x, raw.a[2].y, raw.a[2].z, raw.a[2].w, raw.a[3].x, raw.a[3].y, raw.a[3].z, raw.a[3].w};
 #pragma unroll
-          for (int e = 0; e < 8; ++e) { x0[e] = raw.row32[0][e]; x1[e] = raw.row32[1][e]; }   // rows past the end are zeros
+          for (int e = 0; e < 8; ++e) {
+            x0[e] = ok0 ? __uint_as_float(r0[e]) : 0.f;
+            x1[e] = ok1 ? __uint_as_float(r1[e]) : 0.f;
+          }
         }
       } else {
-        uint4 r0 = raw.row[0], r1 = raw.row[1];
-        if (base_row + key_a >= limit) r0 = make_uint4(0, 0, 0, 0);
-        if (base_row + key_a + 1 >= limit) r1 = make_uint4(0, 0, 0, 0);
+        uint4 r0 = raw.a[0], r1 = raw.a[1];
+        if (!ok0) r0 = make_uint4(0, 0, 0, 0);
+        if (!ok1) r1 = make_uint4(0, 0, 0, 0);
         const uint32_t a4[4] = {r0.x, r0.y, r0.z, r0.w}, b4[4] = {r1.x, r1.y, r1.z, r1.w};
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
@@ -328,31 +357,29 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
           x1[2 * e2] = bf16lo_to_f32(b4[e2]); x1[2 * e2 + 1] = bf16hi_to_f32(b4[e2]);
         }
       }
-      if (role_k) {
+      if constexpr (ROLE_K) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) { x0[e] *= sc; x1[e] *= sc; }
         store_k_split(buf, 0, x0);
         store_k_split(buf, 1, x1);
       } else {
-        store_v_pair(vbuf, x0, x1);
+        store_v_pair(buf, x0, x1);
       }
     }
   };
 
   // ---- one tile: S^T, then softmax and O^T ---------------------------------------------
   const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-  auto compute = [&](auto nbc, int t, int kbuf, int vbuf) __attribute__((always_inline)) {
+  auto compute = [&](auto nbc, int t, int kbuf, int vbuf, bool first) __attribute__((always_inline)) {
     constexpr int NB = decltype(nbc)::value;      // query blocks this wave owns: 1 or 2
-    f32x16 s[2][2];                               // [key half][query block], log2-domain logits
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[mb][nb][r] = 0.f;
+    f32x16 s[2][2];                               // [key half][query block], log2-domain logits minus m
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 qh[NB], ql;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) qh[nb] = __builtin_bit_cast(bf16x8, qbase[(nb * 4 + ks) * 64]);
+      if constexpr (F32IN) ql = __builtin_bit_cast(bf16x8, qbase[(1 * 4 + ks) * 64]);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
         const int aoff = (mb * 32 + l32) * kLdsRow + ks * 16 + hf * 8;
@@ -360,9 +387,10 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
         const bf16x8 al = *reinterpret_cast<const bf16x8*>(lds_klo[kbuf] + aoff);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-          s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qf[nb][ks], s[mb][nb], 0, 0, 0);
-          s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qf[nb][ks], s[mb][nb], 0, 0, 0);
-          if constexpr (F32IN) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qlo[nb][ks], s[mb][nb], 0, 0, 0);
+          if (ks == 0) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qh[nb], negm[nb], 0, 0, 0);
+          else s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qh[nb], s[mb][nb], 0, 0, 0);
+          s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qh[nb], s[mb][nb], 0, 0, 0);
+          if constexpr (F32IN) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, ql, s[mb][nb], 0, 0, 0);
         }
       }
     }
@@ -386,7 +414,8 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     // p = 2^(s - m), packed to f16 as the B operand of the second product, summed into l.
     // The reference m is not checked beforehand: a key that exceeds it by more than the
     // f16 range allows turns its p, and with it the row sum, into infinity; only then
-    // (rare, wave-uniform) are the references raised and the probabilities recomputed.
+    // (rare, wave-uniform), and on the wave's first tile, are the references raised and
+    // the probabilities formed again.
     f16x8 pb[2][4];                   // [query block][16-key step]
     float l_new[2];
     auto probabilities = [&]() __attribute__((always_inline)) {
@@ -399,8 +428,8 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
           uint32_t w[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p0 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e] - m_ref[nb]);
-            const float p1 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e + 1] - m_ref[nb]);
+            const float p0 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e]);
+            const float p1 = __builtin_amdgcn_exp2f(s[mb][nb][r0 + 2 * e + 1]);
             w[e] = pack_f16(p0, p1);
             l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w[e]), ones, l, false);
           }
@@ -409,11 +438,13 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
         l_new[nb] = l;
       }
     };
-    probabilities();
-    bool overflow = false;
+    bool redo = first;                // the first tile sets m from its own keys (m starts at 0)
+    if (!first) {
+      probabilities();
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) overflow |= !(l_new[nb] < kSumLimit);
-    if (__any(overflow)) {
+      for (int nb = 0; nb < NB; ++nb) redo |= !(l_new[nb] < kSumLimit);
+    }
+    if (__any(redo)) {
       // raise the references of the rows whose largest key exceeds them by more than the gap
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
@@ -421,14 +452,20 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
 #pragma unroll
         for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s[0][nb][r]), s[1][nb][r]);
         const float mq = fmaxf(a, __shfl_xor(a, 32));                // both halves of a query agree
-        const float m_new = (mq > m_ref[nb] + kRescaleGap) ? mq : m_ref[nb];
-        const float alpha = __builtin_amdgcn_exp2f(m_ref[nb] - m_new);
-        m_ref[nb] = m_new;
+        const float delta = (first || mq > kRescaleGap) ? mq : 0.f;
+        const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated before the first tile
+        m_ref[nb] += delta;
         l_run[nb] *= alpha;
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[cb][nb][r] *= alpha;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[mb][nb][r] -= delta;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) negm[nb][r] = -m_ref[nb];
       }
       probabilities();
     }
@@ -447,36 +484,48 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     __builtin_amdgcn_s_setprio(0);
   };
   auto run_compute = [&](int t, int buf) __attribute__((always_inline)) {
-    if (nblk == 2) compute(std::integral_constant<int, 2>{}, t, buf, buf);
-    else if (nblk == 1) compute(std::integral_constant<int, 1>{}, t, buf, buf);
+    const bool first = (t == tile_begin);
+    if (nblk == 2) {
+      if constexpr (!F32IN) compute(std::integral_constant<int, 2>{}, t, buf, buf, first);
+    } else if (nblk == 1) {
+      compute(std::integral_constant<int, 1>{}, t, buf, buf, first);
+    }
   };
 
   // ---- tile loop --------------------------------------------------------------------
-  // Between two workgroup barriers waves 0-3 compute tile t and then stage tile t+1, waves
-  // 4-7 stage first and then compute, so the two waves of a SIMD are out of step.  A
-  // tile's codes are loaded one interval before they are decoded.
-  if (tile_begin < tile_end) {
-    load_raw(tile_begin);
-    decode_store(tile_begin, 0, 0);
-    if (tile_begin + 1 < tile_end) load_raw(tile_begin + 1);
+  // Between two workgroup barriers waves 0-3 (K stagers) compute tile t and then stage tile
+  // t+1, waves 4-7 (V stagers) stage first and then compute, so the two waves of a SIMD are
+  // out of step.  A tile's raw data is loaded one interval before it is decoded.
+  auto tile_loop = [&](auto rolec) __attribute__((always_inline)) {
+    constexpr bool ROLE_K = decltype(rolec)::value;
+    TileRaw<ROLE_K ? KB : VB> raw;
+    const int last = tile_end - 1;
+    load_raw(rolec, raw, tile_begin);
+    decode_store(rolec, raw, tile_begin, 0);
+    load_raw(rolec, raw, min(tile_begin + 1, last));
     __syncthreads();
     for (int t = tile_begin; t < tile_end; ++t) {
       const int buf = (t - tile_begin) & 1;
-      const bool more = (t + 1) < tile_end;
-      if (stage_first) {
-        if (more) decode_store(t + 1, buf ^ 1, buf ^ 1);
-        if (t + 2 < tile_end) load_raw(t + 2);
+      const bool more = t < last;
+      if constexpr (ROLE_K) {
         run_compute(t, buf);
+        if (more) decode_store(rolec, raw, t + 1, buf ^ 1);
+        load_raw(rolec, raw, min(t + 2, last));
       } else {
+        if (more) decode_store(rolec, raw, t + 1, buf ^ 1);
+        load_raw(rolec, raw, min(t + 2, last));
         run_compute(t, buf);
-        if (more) decode_store(t + 1, buf ^ 1, buf ^ 1);
-        if (t + 2 < tile_end) load_raw(t + 2);
       }
       __syncthreads();
     }
+  };
+  if (tile_begin < tile_end) {
+    if (role_k) tile_loop(std::true_type{});
+    else tile_loop(std::false_type{});
   }
 
   // ---- epilogue -------------------------------------------------------------------
+  if (tile_begin >= tile_end) m_ref[0] = m_ref[1] = kNegBig;     // an empty key range weighs nothing in the merge
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
     const int qi = (nb < nblk) ? row0 + nb * 32 + l32 : n;
