@@ -34,6 +34,7 @@
 #include "kvx_dev.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace kvx {
 
@@ -106,6 +107,20 @@ __device__ __forceinline__ void load8_f32(const void* base, int64_t off, float (
   const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + off);
   const float4 a = p[0], b = p[1];
   x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+// Scheduling groups (the compiler keeps the groups of a basic block in the order given):
+// Mask 0x008 = MFMA, 0x100 = LDS read.
+template <int Mask, int N>
+__device__ __forceinline__ void sched_group() {
+  if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(Mask, N, 0);
+}
+// Step i of the first product (i = 2 * channel slice + key half): the K reads for step
+// i + AHEAD and, on even steps, the query reads for two slices on, then the step's MFMAs.
+template <int NB, bool F32, int AHEAD, int... I>
+__device__ __forceinline__ void pin_qk_steps(std::integer_sequence<int, I...>) {
+  ((sched_group<0x100, ((I + AHEAD < 8) ? 2 : 0) + (((I & 1) == 0 && (I >> 1) + 2 < 4) ? NB + (F32 ? 1 : 0) : 0)>(),
+    sched_group<0x008, (F32 ? 3 : 2) * NB>()), ...);
 }
 
 template <int KB, int VB, bool F32IN>
@@ -373,27 +388,42 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   auto compute = [&](auto nbc, int t, int kbuf, int vbuf, bool first) __attribute__((always_inline)) {
     constexpr int NB = decltype(nbc)::value;      // query blocks this wave owns: 1 or 2
     f32x16 s[2][2];                               // [key half][query block], log2-domain logits minus m
+    // The operands come from LDS a few steps ahead of the MFMAs that use them (a step =
+    // one key half of one 16-channel slice: the K hi and lo fragments).
+    constexpr int kAhead = NB == 2 ? 2 : 4;
+    bf16x8 ah[8], al[8], qh[4][NB], ql[4];
+    auto read_k = [&](int i) __attribute__((always_inline)) {
+      const int ks = i >> 1, mb = i & 1;
+      const int aoff = (mb * 32 + l32) * kLdsRow + ks * 16 + hf * 8;
+      ah[i] = *reinterpret_cast<const bf16x8*>(lds_khi[kbuf] + aoff);
+      al[i] = *reinterpret_cast<const bf16x8*>(lds_klo[kbuf] + aoff);
+    };
+    auto read_q = [&](int ks) __attribute__((always_inline)) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) qh[ks][nb] = __builtin_bit_cast(bf16x8, qbase[(nb * 4 + ks) * 64]);
+      if constexpr (F32IN) ql[ks] = __builtin_bit_cast(bf16x8, qbase[(1 * 4 + ks) * 64]);
+    };
+    read_q(0);
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) read_k(i);
+    read_q(1);
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 qh[NB], ql;
+    for (int i = 0; i < 8; ++i) {
+      const int ks = i >> 1, mb = i & 1;
+      if (i + kAhead < 8) read_k(i + kAhead);
+      if (mb == 0 && ks + 2 < 4) read_q(ks + 2);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) qh[nb] = __builtin_bit_cast(bf16x8, qbase[(nb * 4 + ks) * 64]);
-      if constexpr (F32IN) ql = __builtin_bit_cast(bf16x8, qbase[(1 * 4 + ks) * 64]);
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        const int aoff = (mb * 32 + l32) * kLdsRow + ks * 16 + hf * 8;
-        const bf16x8 ah = *reinterpret_cast<const bf16x8*>(lds_khi[kbuf] + aoff);
-        const bf16x8 al = *reinterpret_cast<const bf16x8*>(lds_klo[kbuf] + aoff);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          if (ks == 0) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qh[nb], negm[nb], 0, 0, 0);
-          else s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, qh[nb], s[mb][nb], 0, 0, 0);
-          s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qh[nb], s[mb][nb], 0, 0, 0);
-          if constexpr (F32IN) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, ql, s[mb][nb], 0, 0, 0);
-        }
+      for (int nb = 0; nb < NB; ++nb) {
+        if (ks == 0) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], qh[ks][nb], negm[nb], 0, 0, 0);
+        else s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], qh[ks][nb], s[mb][nb], 0, 0, 0);
+        s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], qh[ks][nb], s[mb][nb], 0, 0, 0);
+        if constexpr (F32IN) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], ql[ks], s[mb][nb], 0, 0, 0);
       }
     }
+    // pin the order: the initial reads, then per step the reads issued for later steps and its MFMAs
+    sched_group<0x100, 2 * kAhead + 2 * NB + (F32IN ? 2 : 0)>();
+    pin_qk_steps<NB, F32IN, kAhead>(std::make_integer_sequence<int, 8>{});
     __builtin_amdgcn_s_setprio(0);
 
     int valid;
@@ -418,6 +448,16 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     // the probabilities formed again.
     f16x8 pb[2][4];                   // [query block][16-key step]
     float l_new[2];
+    // V^T fragments of the first two 16-key steps are requested now, the rest while the
+    // second product runs
+    f16x8 vf[4][2];
+    auto read_v = [&](int kk) __attribute__((always_inline)) {
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+        vf[kk][cb] = *reinterpret_cast<const f16x8*>(lds_v[vbuf] + (cb * 32 + l32) * kLdsRow + kk * 16 + hf * 8);
+    };
+    read_v(0);
+    read_v(1);
     auto probabilities = [&]() __attribute__((always_inline)) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
@@ -474,13 +514,16 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
+      if (kk + 2 < 4) read_v(kk + 2);
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        const f16x8 a = *reinterpret_cast<const f16x8*>(lds_v[vbuf] + (cb * 32 + l32) * kLdsRow + kk * 16 + hf * 8);
+      for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[nb][kk], o[cb][nb], 0, 0, 0);
-      }
+        for (int nb = 0; nb < NB; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[kk][cb], pb[nb][kk], o[cb][nb], 0, 0, 0);
     }
+    sched_group<0x100, 4>();
+    sched_group<0x008, 2 * NB>();
+    sched_group<0x100, 4>();
+    sched_group<0x008, 6 * NB>();
     __builtin_amdgcn_s_setprio(0);
   };
   auto run_compute = [&](int t, int buf) __attribute__((always_inline)) {
