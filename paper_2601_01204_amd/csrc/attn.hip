@@ -160,9 +160,10 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   // Query rows of this wave: the tile's q_blocks 32-row blocks are dealt to the 8 waves as
   // evenly as possible (one or two blocks each), so ragged frame sizes load the SIMDs evenly.
   const int blk_base = g.q_blocks >> 3, blk_extra = g.q_blocks & 7;
-  const int blk0 = wave * blk_base + min(wave, blk_extra);
+  const int wq = (wave + 4) & 7;           // the V stagers (lighter decode) take the extra blocks first
+  const int blk0 = wq * blk_base + min(wq, blk_extra);
   const int row0 = (qt * g.q_blocks + blk0) * 32;
-  int nblk = blk_base + (wave < blk_extra ? 1 : 0);
+  int nblk = blk_base + (wq < blk_extra ? 1 : 0);
   if (row0 + 32 >= n) nblk = min(nblk, 1);
   if (row0 >= n) nblk = 0;                        // such a wave only helps with staging
   const bool role_k = wave < 4;            // waves 0-3 stage K, waves 4-7 stage V
