@@ -1,15 +1,15 @@
 // Attention of one frame's queries over [de-quantised cache ; the frame's own K/V]
 // (paper Sec. 3.1 Eq. 1 with the de-quantisation of Sec. 3.3 Eq. 10 fused in).
 //
-// Work decomposition: a workgroup of 8 waves owns a tile of query rows of one head (up to
-// 512, cut so that the frame's 32-row blocks spread evenly over tiles and waves) and a
-// contiguous range of 64-key tiles (split-KV); each wave owns one or two 32-row blocks.  Per tile
-// waves 0-3 de-quantise the K codes and waves 4-7 the V codes once into LDS (K
-// row-major, V transposed), then every wave runs S^T = K Q^T and O^T += V^T P^T on the
-// matrix cores with an online softmax in registers.  Computing the transposed products puts a query
-// in a lane and its keys in that lane's registers, so the probabilities feed the second
-// MFMA straight from registers (the key order inside a 16-key step is a permutation
-// shared by V^T's LDS layout) and the row statistics stay in the lane.
+// Work decomposition: a workgroup owns a tile of up to 12 32-row query blocks of one head
+// (the frame's blocks cut evenly over tiles), one block per wave, so 8 to 12 waves, and a
+// contiguous range of 64-key tiles (split-KV).  Per tile waves 0-3 de-quantise the K
+// codes and waves 4-7 the V codes once into LDS (K row-major, V transposed), then every
+// wave runs S^T = K Q^T and O^T += V^T P^T on the matrix cores with an online softmax in
+// registers.  Computing the transposed products puts a query in a lane and its keys in
+// that lane's registers, so the probabilities feed the second MFMA straight from
+// registers (the key order inside a 16-key step is a permutation shared by V^T's LDS
+// layout) and the row statistics stay in the lane.
 //
 // Precision.  A de-quantised key s * (code - z) is an fp32 value; rounding it to 8
 // significand bits perturbs the logits of the dominant key channels by ~1e-2, far above
@@ -27,10 +27,12 @@
 // than kRescaleGap, O and l are rescaled and the tile's probabilities are formed again.
 //
 // Schedule.  Measured on gfx950, an MFMA overlaps only one or two vector instructions of
-// its own wave but ~20 of its 32 cycles with vector work of the other wave on the SIMD.
-// The two waves a SIMD gets from this workgroup (w and w + 4) therefore run the tile in
-// opposite phase: waves 0-3 compute then stage the next tile, waves 4-7 stage then
-// compute, so one wave's MFMA stretch meets the other's vector stretch.
+// its own wave and about a quarter of its cycles with vector work of other waves, so a
+// SIMD is close to a serial resource and what matters is that it always has a wave that
+// can issue.  A SIMD holds up to three waves of the workgroup (w, w + 4, w + 8), each
+// with the same matrix work; waves 0-3 compute a tile and then stage K of the next one,
+// waves 4-7 stage V first and then compute, waves 8-11 only compute, so their MFMA and
+// vector stretches fall at different times between two barriers.
 #include "kvx_dev.h"
 
 #include <type_traits>
@@ -49,6 +51,7 @@ constexpr int kLdsRow = 72;                       // 16-bit elements per LDS row
 constexpr int kTileElems = kTileK * kLdsRow;      // one K or V^T tile
 constexpr float kNegBig = -1.0e30f;
 constexpr float kRescaleGap = 8.0f;               // log2 units
+constexpr int kAttnMaxWaves = 12;                 // waves (= 32-row query blocks) per workgroup, three per SIMD
 constexpr float kSumLimit = 1.0e37f;              // a row sum at or above this (or NaN) saw an f16 overflow
 
 #define KVX_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -124,7 +127,7 @@ __device__ __forceinline__ void pin_qk_steps(std::integer_sequence<int, I...>) {
 }
 
 template <int KB, int VB, bool F32IN>
-__global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
+__global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   // linear block id -> (query tile, item, split, head); the last query tile (usually a
   // ragged, light one) is dispatched last so it fills in behind the full ones
@@ -143,7 +146,8 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_khi[2][kTileElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_klo[2][kTileElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileElems];
-  __shared__ uint4 lds_q[8 * 2 * 4 * 64];                 // 8 waves x 2 sets x 4 channel steps x 64 lanes
+  constexpr int kQSets = F32IN ? 2 : 1;                   // bf16 queries: one fragment set; fp32: hi and lo
+  __shared__ uint4 lds_q[kAttnMaxWaves * kQSets * 4 * 64];   // waves x sets x 4 channel steps x 64 lanes
 
   const int n = g.n;
   const int t_c = it.t_c;
@@ -157,26 +161,19 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
   const uint8_t* half = cache_half(g, it.cache, it.cur);
   const bool compressed = !g.uncompressed;
   const float sc = g.scale_log2;
-  // Query rows of this wave: the tile's q_blocks 32-row blocks are dealt to the 8 waves as
-  // evenly as possible (one or two blocks each), so ragged frame sizes load the SIMDs evenly.
-  const int blk_base = g.q_blocks >> 3, blk_extra = g.q_blocks & 7;
-  const int wq = (wave + 4) & 7;           // the V stagers (lighter decode) take the extra blocks first
-  const int blk0 = wq * blk_base + min(wq, blk_extra);
-  const int row0 = (qt * g.q_blocks + blk0) * 32;
-  int nblk = blk_base + (wq < blk_extra ? 1 : 0);
-  if (row0 + 32 >= n) nblk = min(nblk, 1);
-  if (row0 >= n) nblk = 0;                        // such a wave only helps with staging
-  const bool role_k = wave < 4;            // waves 0-3 stage K, waves 4-7 stage V
+  // Query rows of this wave: block `wave` of the tile's q_blocks 32-row blocks; a wave
+  // without rows (fewer than 8 blocks in the tile, or a ragged last tile) only stages.
+  constexpr int NB = 1;
+  const int row0 = (qt * g.q_blocks + wave) * 32;
+  const int nblk = (wave < g.q_blocks && row0 < n) ? 1 : 0;
 
   // ---- this wave's query fragments (B operand of S^T = K Q^T) ---------------------
-  // They live in a private LDS region of the wave, one 16-byte entry per lane, fragment
-  // and 16-channel step, and are re-read every tile: the registers they would occupy hold
-  // the -m blocks below instead.  bf16 input: set = query block.  fp32 input (one query
-  // block per wave): set 0 = hi, set 1 = lo part.
-  uint4* qbase = lds_q + (wave * 2 * 4) * 64 + lane;
-#pragma unroll
-  for (int nb = 0; nb < (F32IN ? 1 : 2); ++nb) {
-    const int qi = (nb < nblk) ? row0 + nb * 32 + l32 : n;
+  // They live in a private LDS region of the wave, one 16-byte entry per lane and
+  // 16-channel step (fp32 input: a second set for the lo parts), and are re-read every
+  // tile: the registers they would occupy hold the -m block below instead.
+  uint4* qbase = lds_q + (wave * kQSets * 4) * 64 + lane;
+  {
+    const int qi = nblk ? row0 + l32 : n;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int64_t off = (int64_t)qi * g.tok_stride + (int64_t)h * g.head_stride + ks * 16 + hf * 8;
@@ -191,19 +188,19 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
       } else {
         uint4 v = make_uint4(0, 0, 0, 0);
         if (qi < n) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.q) + off);
-        qbase[(nb * 4 + ks) * 64] = v;
+        qbase[ks * 64] = v;
       }
     }
   }
 
-  f32x16 o[2][2];                     // [channel block][query block]
-  // Per query block: the reference m (lanes l and l + 32 hold the same value), the running
+  f32x16 o[2][NB];                    // [channel block][query block]
+  // Per query block (one here): the reference m (lanes l and l + 32 hold the same value), the running
   // row sum, and a 16-register block filled with -m that the first MFMA of every tile
   // takes as its accumulator input, so S^T leaves the matrix core as s - m.
-  f32x16 negm[2];
-  float m_ref[2], l_run[2];
+  f32x16 negm[NB];
+  float m_ref[NB], l_run[NB];
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
+  for (int nb = 0; nb < NB; ++nb) {
     m_ref[nb] = 0.f;
     l_run[nb] = 0.f;
 #pragma unroll
@@ -386,12 +383,11 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
 
   // ---- one tile: S^T, then softmax and O^T ---------------------------------------------
   const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-  auto compute = [&](auto nbc, int t, int kbuf, int vbuf, bool first) __attribute__((always_inline)) {
-    constexpr int NB = decltype(nbc)::value;      // query blocks this wave owns: 1 or 2
-    f32x16 s[2][2];                               // [key half][query block], log2-domain logits minus m
+  auto compute = [&](int t, int kbuf, int vbuf, bool first) __attribute__((always_inline)) {
+    f32x16 s[2][NB];                               // [key half][query block], log2-domain logits minus m
     // The operands come from LDS a few steps ahead of the MFMAs that use them (a step =
     // one key half of one 16-channel slice: the K hi and lo fragments).
-    constexpr int kAhead = NB == 2 ? 2 : 4;
+    constexpr int kAhead = 3;
     bf16x8 ah[8], al[8], qh[4][NB], ql[4];
     auto read_k = [&](int i) __attribute__((always_inline)) {
       const int ks = i >> 1, mb = i & 1;
@@ -401,7 +397,7 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     };
     auto read_q = [&](int ks) __attribute__((always_inline)) {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) qh[ks][nb] = __builtin_bit_cast(bf16x8, qbase[(nb * 4 + ks) * 64]);
+      for (int nb = 0; nb < NB; ++nb) qh[ks][nb] = __builtin_bit_cast(bf16x8, qbase[ks * 64]);
       if constexpr (F32IN) ql[ks] = __builtin_bit_cast(bf16x8, qbase[(1 * 4 + ks) * 64]);
     };
     read_q(0);
@@ -438,7 +434,6 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
           const int key = mb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
           if (key >= valid) {
             s[mb][0][r] = kNegBig;
-            if (NB == 2) s[mb][1][r] = kNegBig;
           }
         }
     }
@@ -447,8 +442,8 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     // f16 range allows turns its p, and with it the row sum, into infinity; only then
     // (rare, wave-uniform), and on the wave's first tile, are the references raised and
     // the probabilities formed again.
-    f16x8 pb[2][4];                   // [query block][16-key step]
-    float l_new[2];
+    f16x8 pb[NB][4];                  // [query block][16-key step]
+    float l_new[NB];
     // V^T fragments of the first two 16-key steps are requested now, the rest while the
     // second product runs
     f16x8 vf[4][2];
@@ -528,18 +523,13 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     __builtin_amdgcn_s_setprio(0);
   };
   auto run_compute = [&](int t, int buf) __attribute__((always_inline)) {
-    const bool first = (t == tile_begin);
-    if (nblk == 2) {
-      if constexpr (!F32IN) compute(std::integral_constant<int, 2>{}, t, buf, buf, first);
-    } else if (nblk == 1) {
-      compute(std::integral_constant<int, 1>{}, t, buf, buf, first);
-    }
+    if (nblk) compute(t, buf, buf, t == tile_begin);
   };
 
   // ---- tile loop --------------------------------------------------------------------
   // Between two workgroup barriers waves 0-3 (K stagers) compute tile t and then stage tile
-  // t+1, waves 4-7 (V stagers) stage first and then compute, so the two waves of a SIMD are
-  // out of step.  A tile's raw data is loaded one interval before it is decoded.
+  // t+1, waves 4-7 (V stagers) stage first and then compute, the others only compute.  A
+  // tile's raw data is loaded one interval before it is decoded.
   auto tile_loop = [&](auto rolec) __attribute__((always_inline)) {
     constexpr bool ROLE_K = decltype(rolec)::value;
     TileRaw<ROLE_K ? KB : VB> raw;
@@ -564,14 +554,23 @@ __global__ __launch_bounds__(512) void attn_kernel(const KvxBatch b) {
     }
   };
   if (tile_begin < tile_end) {
-    if (role_k) tile_loop(std::true_type{});
-    else tile_loop(std::false_type{});
+    if (wave < 4) {
+      tile_loop(std::true_type{});
+    } else if (wave < 8) {
+      tile_loop(std::false_type{});
+    } else {
+      __syncthreads();
+      for (int t = tile_begin; t < tile_end; ++t) {
+        run_compute(t, (t - tile_begin) & 1);
+        __syncthreads();
+      }
+    }
   }
 
   // ---- epilogue -------------------------------------------------------------------
-  if (tile_begin >= tile_end) m_ref[0] = m_ref[1] = kNegBig;     // an empty key range weighs nothing in the merge
+  if (tile_begin >= tile_end) m_ref[0] = kNegBig;     // an empty key range weighs nothing in the merge
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
+  for (int nb = 0; nb < NB; ++nb) {
     const int qi = (nb < nblk) ? row0 + nb * 32 + l32 : n;
     const float l_tot = l_run[nb] + __shfl_xor(l_run[nb], 32);
     if (g.n_splits == 1) {
@@ -646,8 +645,9 @@ template <int KB, int VB>
 static void launch_attn_t(const KvxBatch& b, hipStream_t st) {
   const Geometry& g = b.g;
   dim3 grid(g.n_qtiles * g.H * b.n_items * g.n_splits);
-  if (g.in_f32) hipLaunchKernelGGL((attn_kernel<KB, VB, true>), grid, dim3(512), 0, st, b);
-  else hipLaunchKernelGGL((attn_kernel<KB, VB, false>), grid, dim3(512), 0, st, b);
+  const dim3 block(64 * (g.q_blocks > 8 ? g.q_blocks : 8));      // a wave per query block, at least the 8 staging waves
+  if (g.in_f32) hipLaunchKernelGGL((attn_kernel<KB, VB, true>), grid, block, 0, st, b);
+  else hipLaunchKernelGGL((attn_kernel<KB, VB, false>), grid, block, 0, st, b);
 }
 
 void launch_attention(const KvxBatch& b, int /*max_tiles*/, hipStream_t st) {

@@ -172,10 +172,9 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   g.out_f32 = c.out_dtype == KV_F32;
   g.uncompressed = unc;
   {
-    // a wave of the attention kernel owns up to two 32-row query blocks (one with fp32
-    // input, whose queries take twice the room as a bf16 hi/lo pair)
+    // an attention workgroup holds up to 12 waves, one 32-row query block each
     const int nblocks = (g.n + 31) / 32;
-    const int tile_blocks = g.in_f32 ? 8 : 16;
+    const int tile_blocks = 12;
     g.n_qtiles = (nblocks + tile_blocks - 1) / tile_blocks;
     g.q_blocks = (nblocks + g.n_qtiles - 1) / g.n_qtiles;
     g.n_pad = g.n_qtiles * g.q_blocks * 32;

@@ -9,7 +9,7 @@ namespace kvx {
 
 constexpr int kHeadDim = 64;        // d; the kernels are written for 64 channels per head
 constexpr int kTileK = 64;          // keys per attention tile / tokens per rebuild block
-constexpr int kQTileMax = 512;      // most query rows per attention workgroup (8 waves x 64)
+constexpr int kQTileMax = 384;      // most query rows per attention workgroup (12 waves x 32)
 constexpr int kMaxItems = 48;       // caches per launch (bounded by the kernel-argument size)
 constexpr int kMaxSplits = 16;      // key-range splits per attention workgroup column
 
@@ -68,7 +68,7 @@ struct Geometry {
   int32_t n_splits;
   int32_t n_pad;          // query rows padded to n_qtiles * q_blocks * 32
   int32_t n_qtiles;       // query tiles (attention workgroups per head and key split)
-  int32_t q_blocks;       // 32-row query blocks per tile (<= 16)
+  int32_t q_blocks;       // 32-row query blocks per tile (<= 12, one per wave)
   float scale_log2;       // softmax scale * log2(e)
 };
 
