@@ -223,68 +223,75 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   const int k_shift = g.k_group == 64 ? 6 : 5;
   const int v_shift = g.v_group == 64 ? 6 : 5;
 
-  // Addresses of tile `tile`'s raw data for this thread, then the loads.  `tile` may be any
-  // tile of the range (a tile past the end is clamped by the caller and simply not decoded).
+  // Every raw load is addressed as a workgroup-uniform base (scalar registers, advanced per
+  // tile by the scalar unit) plus a 32-bit offset of the lane.  For cache tiles the lane
+  // offsets never change; they are computed here once.
+  const uint32_t lo_kc = (uint32_t)(key_a * kKRow + co * KB);                        // K codes, first row
+  const uint32_t lo_km = (uint32_t)((((key_a >> k_shift) * kHeadDim) + co * 8) * 4);  // K scales / zero-points
+  const uint32_t lo_vc = (uint32_t)(key_a * kVRow + co * VB);                        // V codes, first row
+  const uint32_t lo_vr = (uint32_t)(key_a * kVRow);                                  // start of that V code row
+  const uint32_t lo_vm = (uint32_t)((key_a * ngv + ((co * 8) >> v_shift)) * (int)sizeof(VMeta));
+  const uint32_t lo_un = (uint32_t)((key_a * kHeadDim + co * 8) * 2);                // row of an uncompressed cache
+
+  // The loads of tile `tile`'s raw data for this thread.  `tile` may be any tile of the
+  // range (a tile past the end is clamped by the caller and simply not decoded).
   auto load_raw = [&](auto rolec, auto& raw, int tile) __attribute__((always_inline)) {
     constexpr bool ROLE_K = decltype(rolec)::value;
     constexpr int B = ROLE_K ? KB : VB;
     typedef typename Octet<B>::type CodeT;
-    const uint8_t *pa0, *pa1, *pa2, *pa3, *pc0, *pc1, *pm0, *pm1;
+    const uint8_t *bc, *ba, *bz, *bm;          // uniform bases: codes, a[0..1], a[2..3], m
+    uint32_t oc0, oc1, oa0, oa1, oa2, oa3, om0, om1;
     if (tile < ntc && compressed) {
-      const int ja = tile * kTileK + key_a;
-      const int64_t row = (int64_t)h * g.t_cap + ja;
+      const int64_t row0t = (int64_t)h * g.t_cap + tile * kTileK;
       if constexpr (ROLE_K) {
-        pc0 = half + g.lay.k_codes + row * kKRow + co * KB;
-        pc1 = pc0 + kKRow;
-        const int64_t moff = (((int64_t)h * g.g_cap + (ja >> k_shift)) * kHeadDim + co * 8) * 4;
-        pa0 = half + g.lay.k_scale + moff;
-        pa1 = pa0 + 16;
-        pa2 = half + g.lay.k_zero + moff;
-        pa3 = pa2 + 16;
-        pm0 = pm1 = pa0;
+        bc = half + g.lay.k_codes + row0t * kKRow;
+        oc0 = lo_kc; oc1 = lo_kc + kKRow;
+        const int64_t moff = ((int64_t)h * g.g_cap + ((tile * kTileK) >> k_shift)) * (kHeadDim * 4);
+        ba = half + g.lay.k_scale + moff;
+        bz = half + g.lay.k_zero + moff;
+        oa0 = lo_km; oa1 = lo_km + 16; oa2 = lo_km; oa3 = lo_km + 16;
+        bm = ba; om0 = om1 = lo_km;
       } else {
-        const uint8_t* rowp = half + g.lay.v_codes + row * kVRow;
-        pc0 = rowp + co * VB;
-        pc1 = pc0 + kVRow;
-        pm0 = half + g.lay.v_meta + (row * ngv + ((co * 8) >> v_shift)) * (int64_t)sizeof(VMeta);
-        pm1 = pm0 + ngv * (int)sizeof(VMeta);
-        pa0 = pa1 = pa2 = pa3 = rowp;
+        bc = half + g.lay.v_codes + row0t * kVRow;
+        oc0 = lo_vc; oc1 = lo_vc + kVRow;
+        bm = half + g.lay.v_meta + row0t * ngv * (int64_t)sizeof(VMeta);
+        om0 = lo_vm; om1 = lo_vm + ngv * (int)sizeof(VMeta);
+        ba = bz = bc; oa0 = oa1 = oa2 = oa3 = lo_vr;
       }
     } else {
       if (tile < ntc) {
         // uncompressed bf16 cache: rows of 64 bf16; the row after a tile's last valid one is in bounds
-        const int ja = tile * kTileK + key_a;
-        pa0 = half + (ROLE_K ? g.lay.k_codes : g.lay.v_codes) + (((int64_t)h * g.t_cap + ja) * kHeadDim + co * 8) * 2;
-        pa1 = pa0 + kHeadDim * 2;
-        pa2 = pa3 = pa0;
+        ba = half + (ROLE_K ? g.lay.k_codes : g.lay.v_codes) + ((int64_t)h * g.t_cap + tile * kTileK) * (kHeadDim * 2);
+        oa0 = lo_un; oa1 = lo_un + kHeadDim * 2;
+        oa2 = oa3 = oa0;
       } else {
-        const int ia = (tile - ntc) * kTileK + key_a;
-        const int i0 = min(ia, n - 1), i1 = min(ia + 1, n - 1);      // rows past the frame are zeroed when decoded
-        const uint8_t* src = reinterpret_cast<const uint8_t*>(ROLE_K ? it.k : it.v);
-        const int64_t o0 = (int64_t)i0 * g.tok_stride + (int64_t)h * g.head_stride + co * 8;
-        const int64_t o1 = (int64_t)i1 * g.tok_stride + (int64_t)h * g.head_stride + co * 8;
+        const int trow = (tile - ntc) * kTileK;
+        const int lim = n - 1 - trow;                                   // rows past the frame are zeroed when decoded
+        const uint32_t r0 = (uint32_t)min(key_a, lim), r1 = (uint32_t)min(key_a + 1, lim);
+        constexpr uint32_t elt = F32IN ? 4 : 2;
+        ba = reinterpret_cast<const uint8_t*>(ROLE_K ? it.k : it.v) + ((int64_t)trow * g.tok_stride + (int64_t)h * g.head_stride) * elt;
+        const uint32_t ts = (uint32_t)g.tok_stride;
+        const uint32_t q0 = (r0 * ts + co * 8) * elt, q1 = (r1 * ts + co * 8) * elt;
         if constexpr (F32IN) {
-          pa0 = src + o0 * 4; pa1 = pa0 + 16;
-          pa2 = src + o1 * 4; pa3 = pa2 + 16;
+          oa0 = q0; oa1 = q0 + 16; oa2 = q1; oa3 = q1 + 16;
         } else {
-          pa0 = src + o0 * 2;
-          pa1 = src + o1 * 2;
-          pa2 = pa3 = pa0;
+          oa0 = q0; oa1 = q1; oa2 = oa3 = q0;
         }
       }
-      pc0 = pc1 = pm0 = pm1 = pa0;
+      bz = bc = bm = ba;
+      oc0 = oc1 = om0 = om1 = oa0;
     }
-    raw.c[0] = *reinterpret_cast<const CodeT*>(pc0);
-    raw.c[1] = *reinterpret_cast<const CodeT*>(pc1);
-    raw.a[0] = *reinterpret_cast<const uint4*>(pa0);
-    raw.a[1] = *reinterpret_cast<const uint4*>(pa1);
+    raw.c[0] = *reinterpret_cast<const CodeT*>(bc + oc0);
+    raw.c[1] = *reinterpret_cast<const CodeT*>(bc + oc1);
+    raw.a[0] = *reinterpret_cast<const uint4*>(ba + oa0);
+    raw.a[1] = *reinterpret_cast<const uint4*>(ba + oa1);
     if constexpr (ROLE_K || F32IN) {
-      raw.a[2] = *reinterpret_cast<const uint4*>(pa2);
-      raw.a[3] = *reinterpret_cast<const uint4*>(pa3);
+      raw.a[2] = *reinterpret_cast<const uint4*>(bz + oa2);
+      raw.a[3] = *reinterpret_cast<const uint4*>(bz + oa3);
     }
     if constexpr (!ROLE_K) {
-      raw.m[0] = *reinterpret_cast<const uint2*>(pm0);
-      raw.m[1] = *reinterpret_cast<const uint2*>(pm1);
+      raw.m[0] = *reinterpret_cast<const uint2*>(bm + om0);
+      raw.m[1] = *reinterpret_cast<const uint2*>(bm + om1);
     }
   };
 
