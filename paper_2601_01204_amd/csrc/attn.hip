@@ -70,9 +70,9 @@ __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
 // Two fp32 values -> packed bf16 truncations (hi) and packed bf16 truncated remainders (lo).
 __device__ __forceinline__ void split_bf16(float a, float b, uint32_t& hi, uint32_t& lo) {
   const uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-  hi = (ua >> 16) | (ub & 0xFFFF0000u);
+  hi = __builtin_amdgcn_perm(ub, ua, 0x07060302u);          // the upper halves of a (low) and b (high)
   const float ra = a - __uint_as_float(ua & 0xFFFF0000u), rb = b - __uint_as_float(ub & 0xFFFF0000u);
-  lo = (__float_as_uint(ra) >> 16) | (__float_as_uint(rb) & 0xFFFF0000u);
+  lo = __builtin_amdgcn_perm(__float_as_uint(rb), __float_as_uint(ra), 0x07060302u);
 }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
@@ -88,6 +88,34 @@ __device__ __forceinline__ int octet_code(const typename Octet<B>::type& w, int 
   if constexpr (B == 4) return (int)((w >> (4 * e)) & 0xFu);
   else if constexpr (B == 2) return (int)(((uint32_t)w >> (2 * e)) & 0x3u);
   else return (int)(((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xFFu);
+}
+
+// The same eight codes as floats.  Bytes convert in one instruction each, so 4-bit codes
+// are first spread into the bytes of two words (even and odd channels).
+// Byte K of a word as a float (v_cvt_f32_ubyteK; written out because the compiler would
+// otherwise merge the nibble masks below back into one bit-field extract per value).
+template <int K>
+__device__ __forceinline__ float byte_to_float(uint32_t w) {
+  float f;
+  if constexpr (K == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(f) : "v"(w));
+  else if constexpr (K == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(f) : "v"(w));
+  else if constexpr (K == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(f) : "v"(w));
+  else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(f) : "v"(w));
+  return f;
+}
+template <int B>
+__device__ __forceinline__ void octet_floats(const typename Octet<B>::type& w, float (&f)[8]) {
+  if constexpr (B == 8) {
+    f[0] = byte_to_float<0>(w.x); f[1] = byte_to_float<1>(w.x); f[2] = byte_to_float<2>(w.x); f[3] = byte_to_float<3>(w.x);
+    f[4] = byte_to_float<0>(w.y); f[5] = byte_to_float<1>(w.y); f[6] = byte_to_float<2>(w.y); f[7] = byte_to_float<3>(w.y);
+  } else if constexpr (B == 4) {
+    const uint32_t ev = w & 0x0F0F0F0Fu, od = (w >> 4) & 0x0F0F0F0Fu;
+    f[0] = byte_to_float<0>(ev); f[2] = byte_to_float<1>(ev); f[4] = byte_to_float<2>(ev); f[6] = byte_to_float<3>(ev);
+    f[1] = byte_to_float<0>(od); f[3] = byte_to_float<1>(od); f[5] = byte_to_float<2>(od); f[7] = byte_to_float<3>(od);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = (float)(((uint32_t)w >> (2 * e)) & 0x3u);
+  }
 }
 
 // Staging registers of one thread: two rows x eight channels of K (waves 0-3) or of V
@@ -314,40 +342,40 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   auto decode_store = [&](auto rolec, const auto& raw, int tile, int buf) __attribute__((always_inline)) {
     constexpr bool ROLE_K = decltype(rolec)::value;
     if (tile < ntc && compressed) {
+      // s * (code - z) evaluated as fma(code, s, -z * s): one conversion and one fused
+      // operation per value (the result differs from Eq. 10's by a rounding of z * s, far
+      // below what the bf16 pair or the f16 value keeps)
       const int ja = tile * kTileK + key_a;
-      const bool full = (tile + 1) * kTileK <= t_c;
+      const bool full = (tile + 1) * kTileK <= t_c;       // uniform; only a cache's last tile can be ragged
       if constexpr (ROLE_K) {
         const uint32_t sw[8] = {raw.a[0].x, raw.a[0].y, raw.a[0].z, raw.a[0].w, raw.a[1].x, raw.a[1].y, raw.a[1].z, raw.a[1].w};
         const uint32_t zw[8] = {raw.a[2].x, raw.a[2].y, raw.a[2].z, raw.a[2].w, raw.a[3].x, raw.a[3].y, raw.a[3].z, raw.a[3].w};
-        float sk[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sk[e] = __uint_as_float(sw[e]) * sc;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          float x[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) x[e] = sk[e] * (float)(octet_code<KB>(raw.c[i], e) - (int32_t)zw[e]);
-          if (!full && (ja + i) >= t_c) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = 0.f;
-          }
-          store_k_split(buf, i, x);
-        }
-      } else {
-        const float s0 = __uint_as_float(raw.m[0].x), s1 = __uint_as_float(raw.m[1].x);
-        const int32_t z0 = (int32_t)raw.m[0].y, z1 = (int32_t)raw.m[1].y;
-        float va[8], vb[8];
+        float sk[8], nz[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          va[e] = s0 * (float)(octet_code<VB>(raw.c[0], e) - z0);
-          vb[e] = s1 * (float)(octet_code<VB>(raw.c[1], e) - z1);
+          sk[e] = __uint_as_float(sw[e]) * sc;
+          nz[e] = -(float)(int32_t)zw[e] * sk[e];
         }
-        if (!full) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            if (ja >= t_c) va[e] = 0.f;
-            if (ja + 1 >= t_c) vb[e] = 0.f;
-          }
+        for (int i = 0; i < 2; ++i) {
+          float f[8], x[8];
+          octet_floats<KB>(raw.c[i], f);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(f[e], sk[e], nz[e]);
+          store_k_split(buf, i, x);        // rows past the cache's end hold finite stale values; their logits are masked
+        }
+      } else {
+        // rows past the cache's end become zeros (scale and offset zero): their probabilities are zero too
+        const bool ok0 = full || ja < t_c, ok1 = full || ja + 1 < t_c;
+        const float s0 = ok0 ? __uint_as_float(raw.m[0].x) : 0.f, s1 = ok1 ? __uint_as_float(raw.m[1].x) : 0.f;
+        const float nz0 = -(float)(int32_t)raw.m[0].y * s0, nz1 = -(float)(int32_t)raw.m[1].y * s1;
+        float fa[8], fb[8], va[8], vb[8];
+        octet_floats<VB>(raw.c[0], fa);
+        octet_floats<VB>(raw.c[1], fb);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          va[e] = __builtin_fmaf(fa[e], s0, nz0);
+          vb[e] = __builtin_fmaf(fb[e], s1, nz1);
         }
         store_v_pair(buf, va, vb);
       }
