@@ -651,20 +651,32 @@ __global__ __launch_bounds__(256) void combine_kernel(const KvxBatch b) {
   const int qi = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int c = (threadIdx.x & 15) * 4;
   if (qi >= g.n) return;
-  float m_max = kNegBig;
-  for (int s = 0; s < g.n_splits; ++s) {
-    const int64_t row = ((int64_t)(blockIdx.z * g.n_splits + s) * g.H + h) * g.n_pad + qi;
-    m_max = fmaxf(m_max, g.part_ml[row * 2]);
+  // all partials are requested before any is used
+  const int64_t row0 = ((int64_t)blockIdx.z * g.n_splits * g.H + h) * g.n_pad + qi;
+  const int64_t row_step = (int64_t)g.H * g.n_pad;
+  float2 ml[kMaxSplits];
+  float4 po[kMaxSplits];
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) {
+    if (s < g.n_splits) {
+      const int64_t row = row0 + s * row_step;
+      ml[s] = *reinterpret_cast<const float2*>(g.part_ml + row * 2);
+      po[s] = *reinterpret_cast<const float4*>(g.part_o + row * kHeadDim + c);
+    }
   }
+  float m_max = kNegBig;
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s)
+    if (s < g.n_splits) m_max = fmaxf(m_max, ml[s].x);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float l = 0.f;
-  for (int s = 0; s < g.n_splits; ++s) {
-    const int64_t row = ((int64_t)(blockIdx.z * g.n_splits + s) * g.H + h) * g.n_pad + qi;
-    const float2 ml = *reinterpret_cast<const float2*>(g.part_ml + row * 2);
-    const float w = __builtin_amdgcn_exp2f(ml.x - m_max);
-    const float4 po = *reinterpret_cast<const float4*>(g.part_o + row * kHeadDim + c);
-    acc.x += w * po.x; acc.y += w * po.y; acc.z += w * po.z; acc.w += w * po.w;
-    l += w * ml.y;
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) {
+    if (s < g.n_splits) {
+      const float w = __builtin_amdgcn_exp2f(ml[s].x - m_max);
+      acc.x += w * po[s].x; acc.y += w * po[s].y; acc.z += w * po[s].z; acc.w += w * po[s].w;
+      l += w * ml[s].y;
+    }
   }
   const float inv = 1.0f / l;
   const int64_t off = (int64_t)qi * g.out_tok_stride + (int64_t)h * g.out_head_stride + c;

@@ -9,6 +9,8 @@
 // even.  A constant group takes s = |min| (1 when min is 0).
 #include "kvx_dev.h"
 
+#include <algorithm>
+
 namespace kvx {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
@@ -282,36 +284,62 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   }
 }
 
-// Values and token ids.  One block = 64 consecutive positions of the next cache for one
-// head.  Surviving tokens carry their codes and (s, z); tokens of the new frame are
-// quantised per token over groups of v_group channels.
+// Values and token ids.  The next cache's positions [0, t_new - n) are surviving tokens,
+// whose codes and (s, z) are carried; the last n positions are the new frame, quantised
+// per token over groups of v_group channels.  Two kinds of blocks share the launch: copy
+// blocks (a lane moves 16 bytes of one token's code row of one head, so 1, 2 or 4 lanes
+// per row, and the row's metadata) and quantise blocks (64 new tokens per block, four
+// lanes per token).
+
 template <int B>
-__global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b) {
+__global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_copy_blocks) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
   const int t_c = it.t_c;
   const int t_new = min(t_c + g.n, g.budget);
+  const int t_keep = t_new - g.n;          // survivors
   const int tid = threadIdx.x;
-  const int r = tid >> 2, cb = tid & 3;
-  const int p = blockIdx.x * kTileK + r;
-  const bool active = p < t_new;           // uniform over each group of 4 lanes
   const uint8_t* cur = cache_half(g, it.cache, it.cur);
   uint8_t* nxt = cache_half(g, it.cache, it.cur ^ 1);
   const int32_t* keep = reinterpret_cast<const int32_t*>(cache_scratch(g, it.cache) + g.sl.keep);
   constexpr int kRow = 8 * B;
-  const int levels = (1 << B) - 1;
   const int ngv = kHeadDim / g.v_group;    // 1 or 2
-  const int lanes_per_group = 4 / ngv;     // 4 or 2 lanes share one value group
-  const int gv = cb / lanes_per_group;
 
-  int src = 0;
-  if (active) src = it.prune ? keep[p] : p;
-  const bool is_new = active && src >= t_c;
+  if ((int)blockIdx.x < n_copy_blocks) {
+    constexpr int kLanes = kRow / 16;                      // lanes per row, 16 bytes of codes each
+    const int p = blockIdx.x * (256 / kLanes) + tid / kLanes;
+    const int part = tid % kLanes;
+    if (p >= t_keep) return;
+    const int src = it.prune ? keep[p] : p;
+    const uint4 w = *reinterpret_cast<const uint4*>(cur + g.lay.v_codes + ((int64_t)h * g.t_cap + src) * kRow + part * 16);
+    const VMeta* ms = reinterpret_cast<const VMeta*>(cur + g.lay.v_meta) + ((int64_t)h * g.t_cap + src) * ngv;
+    VMeta* md = reinterpret_cast<VMeta*>(nxt + g.lay.v_meta) + ((int64_t)h * g.t_cap + p) * ngv;
+    if (kLanes == 1) {
+      md[0] = ms[0];
+      if (ngv == 2) md[1] = ms[1];
+    } else if (part < ngv) {
+      md[part] = ms[part];
+    }
+    *reinterpret_cast<uint4*>(nxt + g.lay.v_codes + ((int64_t)h * g.t_cap + p) * kRow + part * 16) = w;
+    if (h == 0 && part == 0) {
+      const int32_t* ids = reinterpret_cast<const int32_t*>(cur + g.lay.ids);
+      reinterpret_cast<int32_t*>(nxt + g.lay.ids)[p] = ids[src];
+    }
+    return;
+  }
+
+  const int levels = (1 << B) - 1;
+  const int lanes_per_group = 4 / ngv;     // 4 or 2 lanes share one value group
+  const int r = tid >> 2, cb = tid & 3;
+  const int i_new = ((int)blockIdx.x - n_copy_blocks) * kTileK + r;     // token of the new frame
+  const bool active = i_new < g.n;         // uniform over each group of 4 lanes
+  const int p = t_keep + i_new;
+  const int gv = cb / lanes_per_group;
   float x[16];
   float mn = INFINITY, mx = -INFINITY;
-  if (is_new) {
-    load_input16(it.v, (int64_t)(src - t_c) * g.tok_stride + (int64_t)h * g.head_stride + cb * 16, g.in_f32, x);
+  if (active) {
+    load_input16(it.v, (int64_t)i_new * g.tok_stride + (int64_t)h * g.head_stride + cb * 16, g.in_f32, x);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       mn = fminf(mn, x[e]);
@@ -326,37 +354,21 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b) {
     mx = fmaxf(mx, __shfl_xor(mx, 2));
   }
   if (!active) return;
-  uint8_t* dst = nxt + g.lay.v_codes + ((int64_t)h * g.t_cap + p) * kRow + cb * 2 * B;
-  VMeta* mdst = reinterpret_cast<VMeta*>(nxt + g.lay.v_meta) + ((int64_t)h * g.t_cap + p) * ngv + gv;
-  if (is_new) {
-    float s;
-    int32_t z;
-    quant_params(mn, mx, levels, s, z);
-    int code[16];
-    const Divider dv = make_divider(s);
+  float s;
+  int32_t z;
+  quant_params(mn, mx, levels, s, z);
+  int code[16];
+  const Divider dv = make_divider(s);
 #pragma unroll
-    for (int e = 0; e < 16; ++e) code[e] = quant_code_div(x[e], dv, z, levels);
-    pack16<B>(code, dst);
-    if ((cb % lanes_per_group) == 0) {
-      VMeta m;
-      m.s = s;
-      m.z = z;
-      *mdst = m;
-    }
-  } else {
-    uint32_t w[4] = {0, 0, 0, 0};
-    unpack16<B>(cur + g.lay.v_codes + ((int64_t)h * g.t_cap + src) * kRow + cb * 2 * B, w);
-    if constexpr (B == 2) *reinterpret_cast<uint32_t*>(dst) = w[0];
-    else if constexpr (B == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
-    else *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
-    if ((cb % lanes_per_group) == 0)
-      *mdst = (reinterpret_cast<const VMeta*>(cur + g.lay.v_meta))[((int64_t)h * g.t_cap + src) * ngv + gv];
+  for (int e = 0; e < 16; ++e) code[e] = quant_code_div(x[e], dv, z, levels);
+  pack16<B>(code, nxt + g.lay.v_codes + ((int64_t)h * g.t_cap + p) * kRow + cb * 2 * B);
+  if ((cb % lanes_per_group) == 0) {
+    VMeta m;
+    m.s = s;
+    m.z = z;
+    reinterpret_cast<VMeta*>(nxt + g.lay.v_meta)[((int64_t)h * g.t_cap + p) * ngv + gv] = m;
   }
-  if (h == 0 && cb == 0) {
-    const int32_t* ids = reinterpret_cast<const int32_t*>(cur + g.lay.ids);
-    int32_t* ids_n = reinterpret_cast<int32_t*>(nxt + g.lay.ids);
-    ids_n[p] = (src < t_c) ? ids[src] : it.frame * g.n + (src - t_c);
-  }
+  if (h == 0 && cb == 0) reinterpret_cast<int32_t*>(nxt + g.lay.ids)[p] = it.frame * g.n + i_new;
 }
 
 // Uncompressed baseline: append the frame's K and V as bf16 rows [H][t_cap][64].
@@ -405,11 +417,13 @@ void launch_rebuild_k(const KvxBatch& b, int max_tnew, hipStream_t st) {
 }
 
 void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st) {
-  dim3 grid((max_tnew + kTileK - 1) / kTileK, b.g.H, b.n_items);
+  const int rows_per_block = 256 / (b.g.v_bits / 2);           // 16 bytes of codes per lane
+  const int n_copy_blocks = (std::max(max_tnew - b.g.n, 0) + rows_per_block - 1) / rows_per_block;
+  dim3 grid(n_copy_blocks + (b.g.n + kTileK - 1) / kTileK, b.g.H, b.n_items);
   switch (b.g.v_bits) {
-    case 2: hipLaunchKernelGGL(rebuild_v_kernel<2>, grid, dim3(256), 0, st, b); break;
-    case 4: hipLaunchKernelGGL(rebuild_v_kernel<4>, grid, dim3(256), 0, st, b); break;
-    default: hipLaunchKernelGGL(rebuild_v_kernel<8>, grid, dim3(256), 0, st, b); break;
+    case 2: hipLaunchKernelGGL(rebuild_v_kernel<2>, grid, dim3(256), 0, st, b, n_copy_blocks); break;
+    case 4: hipLaunchKernelGGL(rebuild_v_kernel<4>, grid, dim3(256), 0, st, b, n_copy_blocks); break;
+    default: hipLaunchKernelGGL(rebuild_v_kernel<8>, grid, dim3(256), 0, st, b, n_copy_blocks); break;
   }
 }
 

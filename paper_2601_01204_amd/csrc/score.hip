@@ -11,9 +11,6 @@ namespace kvx {
 // Eq. 2-3: one block per pooled row, one thread per (head, channel).  Per (head, channel):
 // add the row's tokens in ascending order starting from the first, divide by the group
 // size; then per channel add heads 0..H-1 in order starting from zero, divide by H.
-// The block that finishes last (a counter in the cache's scratch tells) also forms the row
-// mean of Eq. 6 pulled inside the product: pooled rows added in ascending order from zero,
-// divided by N_pooled.
 __global__ __launch_bounds__(1024) void pool_rows_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.y];
@@ -28,7 +25,6 @@ __global__ __launch_bounds__(1024) void pool_rows_kernel(const KvxBatch b) {
     e = min(a + g.pool_group, g.n);
   }
   __shared__ float pooled[64][kHeadDim];     // up to 64 heads
-  __shared__ int is_last;
   const int c = threadIdx.x & 63;
   for (int h = threadIdx.x >> 6; h < g.H; h += 16) {
     float acc;
@@ -47,27 +43,27 @@ __global__ __launch_bounds__(1024) void pool_rows_kernel(const KvxBatch b) {
     pooled[h][c] = acc / (float)(e - a);
   }
   __syncthreads();
-  uint8_t* sc = cache_scratch(g, it.cache);
-  float* qbar = reinterpret_cast<float*>(sc + g.sl.qbar);
-  int32_t* sel = reinterpret_cast<int32_t*>(sc + g.sl.sel);
   if (threadIdx.x < 64) {
     float acc = 0.f;
     for (int h = 0; h < g.H; ++h) acc = acc + pooled[h][c];
-    qbar[row * kHeadDim + c] = acc / (float)g.H;
-    __threadfence();                          // the row is visible before the counter moves
+    reinterpret_cast<float*>(cache_scratch(g, it.cache) + g.sl.qbar)[row * kHeadDim + c] = acc / (float)g.H;
   }
-  __syncthreads();
-  if (threadIdx.x == 0) is_last = (atomicAdd(&sel[4], 1) == (int)gridDim.x - 1);
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  if (threadIdx.x < 64) {
-    float acc = 0.f;
+}
+
+// The row mean of Eq. 6 pulled inside the product: q~ = (pooled rows added in ascending
+// order from zero) / N_pooled, one thread per channel.  A kernel of its own, so that the
+// pooled rows reach it through the kernel boundary and no block has to fence.
+__global__ __launch_bounds__(64) void pool_mean_kernel(const KvxBatch b) {
+  const Geometry& g = b.g;
+  const Item it = b.items[blockIdx.x];
+  if (!it.prune) return;
+  uint8_t* sc = cache_scratch(g, it.cache);
+  const float* qbar = reinterpret_cast<const float*>(sc + g.sl.qbar);
+  const int c = threadIdx.x;
+  float acc = 0.f;
 #pragma unroll 16
-    for (int i = 0; i < g.n_pooled; ++i) acc = acc + __builtin_nontemporal_load(qbar + i * kHeadDim + c);
-    reinterpret_cast<float*>(sc + g.sl.qt)[c] = acc / (float)g.n_pooled;
-    if (threadIdx.x == 0) sel[4] = 0;         // ready for the next step
-  }
+  for (int i = 0; i < g.n_pooled; ++i) acc = acc + qbar[i * kHeadDim + c];
+  reinterpret_cast<float*>(sc + g.sl.qt)[c] = acc / (float)g.n_pooled;
 }
 
 template <int B>
@@ -132,6 +128,7 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
 
 void launch_pool(const KvxBatch& b, hipStream_t st) {
   hipLaunchKernelGGL(pool_rows_kernel, dim3(b.g.n_pooled, b.n_items), dim3(1024), 0, st, b);
+  hipLaunchKernelGGL(pool_mean_kernel, dim3(b.n_items), dim3(64), 0, st, b);
 }
 
 void launch_score(const KvxBatch& b, int max_tc, hipStream_t st) {
