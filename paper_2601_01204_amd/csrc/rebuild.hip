@@ -160,7 +160,8 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   const int r = tid >> 2, cb = tid & 3;                // row in block, 16-channel block
   const int p = p0 + r;
   const bool active = p < t_new;
-  const int grp = p / g.k_group;
+  const int k_shift = g.k_group == 64 ? 6 : 5;       // groups of 64 or 32 tokens
+  const int grp = p >> k_shift;
   const bool carried = grp < g0;
 
   __shared__ __attribute__((aligned(16))) float vals[kTileK][kHeadDim + 4];
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
     if (src < t_c) {
       unpack16<B>(cur + g.lay.k_codes + ((int64_t)h * g.t_cap + src) * kRow + cb * 2 * B, wsrc);
       if (!carried) {
-        const int sg = src / g.k_group;
+        const int sg = src >> k_shift;
         const int64_t moff = ((int64_t)h * g.g_cap + sg) * kHeadDim + cb * 16;
         const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(cur + g.lay.k_scale) + moff);
         const int4* zp = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(cur + g.lay.k_zero) + moff);
@@ -207,11 +208,20 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   {
     const int c = tid & 63, qtr = tid >> 6;
     float mn = INFINITY, mx = -INFINITY;
-    for (int rr = qtr * 16; rr < qtr * 16 + 16; ++rr) {
-      if (p0 + rr < t_new) {
-        const float v = vals[rr][c];
+    if (p0 + kTileK <= t_new) {                       // all rows present: no per-row test
+#pragma unroll
+      for (int rr = 0; rr < 16; ++rr) {
+        const float v = vals[qtr * 16 + rr][c];
         mn = fminf(mn, v);
         mx = fmaxf(mx, v);
+      }
+    } else {
+      for (int rr = qtr * 16; rr < qtr * 16 + 16; ++rr) {
+        if (p0 + rr < t_new) {
+          const float v = vals[rr][c];
+          mn = fminf(mn, v);
+          mx = fmaxf(mx, v);
+        }
       }
     }
     pmin[qtr][c] = mn;
@@ -219,11 +229,11 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   }
   __syncthreads();
 
-  const int groups_in_block = kTileK / g.k_group;      // 1 or 2
+  const int groups_in_block = kTileK >> k_shift;       // 1 or 2
   if (tid < groups_in_block * 64) {
     const int gi = tid >> 6, c = tid & 63;
-    const int ggrp = p0 / g.k_group + gi;
-    const int first_row = gi * g.k_group;
+    const int ggrp = (p0 >> k_shift) + gi;
+    const int first_row = gi << k_shift;
     if (p0 + first_row < t_new) {
       const int64_t moff = ((int64_t)h * g.g_cap + ggrp) * kHeadDim + c;
       float s;
@@ -232,7 +242,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
         s = reinterpret_cast<const float*>(cur + g.lay.k_scale)[moff];
         z = reinterpret_cast<const int32_t*>(cur + g.lay.k_zero)[moff];
       } else {
-        const int q_lo = first_row / 16, q_hi = (first_row + g.k_group) / 16;
+        const int q_lo = first_row >> 4, q_hi = (first_row + g.k_group) >> 4;
         float mn = INFINITY, mx = -INFINITY;
         for (int qq = q_lo; qq < q_hi; ++qq) {
           mn = fminf(mn, pmin[qq][c]);
@@ -259,7 +269,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
       else if constexpr (B == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(wsrc[0], wsrc[1]);
       else *reinterpret_cast<uint4*>(dst) = make_uint4(wsrc[0], wsrc[1], wsrc[2], wsrc[3]);
     } else {
-      const int gi = r / g.k_group;
+      const int gi = r >> k_shift;
       int code[16];
       if (unsafe_scales) {                      // block-uniform and rare
 #pragma unroll

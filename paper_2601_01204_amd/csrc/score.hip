@@ -91,8 +91,9 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
   __shared__ __attribute__((aligned(16))) int32_t s_z[8][kHeadDim];
   __shared__ __attribute__((aligned(16))) float s_q[kHeadDim];
 
-  const int groups_in_block = 256 / g.k_group;     // 4 or 8
-  const int grp0 = j0 / g.k_group;
+  const int k_shift = g.k_group == 64 ? 6 : 5;      // groups of 64 or 32 tokens
+  const int groups_in_block = 256 >> k_shift;      // 4 or 8
+  const int grp0 = j0 >> k_shift;
   for (int i = threadIdx.x; i < groups_in_block * kHeadDim; i += 256) {
     const int gi = i >> 6, c = i & 63;
     const int grp = grp0 + gi;
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
   const uint32_t* src = reinterpret_cast<const uint32_t*>(half + g.lay.k_codes + ((int64_t)h * g.t_cap + j) * (8 * B));
 #pragma unroll
   for (int i = 0; i < kRowWords; ++i) w[i] = src[i];
-  const int gi = (j - j0) / g.k_group;
+  const int gi = (j - j0) >> k_shift;
   float p[kHeadDim];
 #pragma unroll
   for (int c = 0; c < kHeadDim; ++c) {
