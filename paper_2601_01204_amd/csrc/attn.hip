@@ -134,12 +134,6 @@ struct TileRaw {
   uint2 m[2];
 };
 
-__device__ __forceinline__ void load8_f32(const void* base, int64_t off, float (&x)[8]) {
-  const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + off);
-  const float4 a = p[0], b = p[1];
-  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-}
-
 // Scheduling groups (the compiler keeps the groups of a basic block in the order given):
 // Mask 0x008 = MFMA, 0x100 = LDS read.
 template <int Mask, int N>
@@ -199,27 +193,40 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   // They live in a private LDS region of the wave, one 16-byte entry per lane and
   // 16-channel step (fp32 input: a second set for the lo parts), and are re-read every
   // tile: the registers they would occupy hold the -m block below instead.
+  // They are loaded together with the first tile's raw data, so that the two global
+  // latencies overlap (rows past the frame repeat its last row; their output is not stored).
   uint4* qbase = lds_q + (wave * kQSets * 4) * 64 + lane;
-  {
-    const int qi = nblk ? row0 + l32 : n;
+  auto stage_q = [&]() __attribute__((always_inline)) {
+    if (!nblk) return;
+    const int qi = min(row0 + l32, n - 1);
+    const uint8_t* qrow = reinterpret_cast<const uint8_t*>(it.q) +
+                          ((int64_t)qi * g.tok_stride + (int64_t)h * g.head_stride + hf * 8) * (F32IN ? 4 : 2);
+    if constexpr (F32IN) {
+      uint4 a[4], c[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int64_t off = (int64_t)qi * g.tok_stride + (int64_t)h * g.head_stride + ks * 16 + hf * 8;
-      if constexpr (F32IN) {
-        float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (qi < n) load8_f32(it.q, off, x);
+      for (int ks = 0; ks < 4; ++ks) {
+        a[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 64);
+        c[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 64 + 16);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const float x[8] = {__uint_as_float(a[ks].x), __uint_as_float(a[ks].y), __uint_as_float(a[ks].z), __uint_as_float(a[ks].w),
+                            __uint_as_float(c[ks].x), __uint_as_float(c[ks].y), __uint_as_float(c[ks].z), __uint_as_float(c[ks].w)};
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) split_bf16(x[2 * e], x[2 * e + 1], hi[e], lo[e]);
         qbase[(0 * 4 + ks) * 64] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
         qbase[(1 * 4 + ks) * 64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-      } else {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (qi < n) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.q) + off);
-        qbase[ks * 64] = v;
       }
+    } else {
+      const uint4 q0 = *reinterpret_cast<const uint4*>(qrow), q1 = *reinterpret_cast<const uint4*>(qrow + 32);
+      const uint4 q2 = *reinterpret_cast<const uint4*>(qrow + 64), q3 = *reinterpret_cast<const uint4*>(qrow + 96);
+      qbase[0 * 64] = q0;
+      qbase[1 * 64] = q1;
+      qbase[2 * 64] = q2;
+      qbase[3 * 64] = q3;
     }
-  }
+  };
 
   f32x16 o[2][NB];                    // [channel block][query block]
   // Per query block (one here): the reference m (lanes l and l + 32 hold the same value), the running
@@ -570,6 +577,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
     TileRaw<ROLE_K ? KB : VB> raw;
     const int last = tile_end - 1;
     load_raw(rolec, raw, tile_begin);
+    stage_q();
     decode_store(rolec, raw, tile_begin, 0);
     load_raw(rolec, raw, min(tile_begin + 1, last));
     __syncthreads();
@@ -594,6 +602,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
     } else if (wave < 8) {
       tile_loop(std::false_type{});
     } else {
+      stage_q();
       __syncthreads();
       for (int t = tile_begin; t < tile_end; ++t) {
         run_compute(t, (t - tile_begin) & 1);
