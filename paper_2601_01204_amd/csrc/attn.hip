@@ -157,26 +157,22 @@ __device__ __forceinline__ void to_stored_order(const float (&x)[16], float (&y)
   to_stored_order<B>(x, y, std::make_integer_sequence<int, 16>{});
 }
 
-// Staging registers of one thread as loaded, before decoding.  Every tile fills the same
-// registers with the same straight-line sequence of loads, whatever the tile holds (only the
-// addresses are selected), so the loads of a later tile stay in flight across the barriers.
-// Registers a tile does not use are loaded from a valid dummy address.
+// Staging registers of one thread as loaded, before decoding.  A tile's raw data is loaded
+// one barrier interval before it is decoded and stays in flight across the barrier.
 // Key role: one key row x sixteen channels.
-//   cached tile : c = the codes, a[0..1] / a[2..3] / a[4..5] = the slice's a, b and 1024 + z as
-//                 f16 in stored order, flag = the group's plain-path flag
+//   cached tile : c = the codes (the group's metadata block reaches the key waves through LDS)
 //   bf16 row    : a[0..1] (own frame, uncompressed cache);  fp32 row: a[0..3] (own frame)
-template <int B>
+template <int B, bool F32>
 struct KRaw {
-  uint4 a[6];
+  uint4 a[F32 ? 4 : 2];
   typename Hexdec<B>::type c;
-  uint32_t flag;
 };
 // Value role: two key rows x eight channels.
 //   cached tile : c = the two rows' codes, m = the two rows' (scale, zero-point)
 //   bf16 rows   : a[0], a[1] = the two rows;  fp32 rows: a[0..1] = first row, a[2..3] = second row
-template <int B>
+template <int B, bool F32>
 struct VRaw {
-  uint4 a[4];
+  uint4 a[F32 ? 4 : 2];
   typename Octet<B>::type c[2];
   uint2 m[2];
 };
@@ -219,6 +215,9 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileElems];
   constexpr int kQSets = F32IN ? 2 : 1;                   // bf16 queries: one fragment set; fp32: hi and lo
   __shared__ uint4 lds_q[kAttnMaxWaves * kQSets * 4 * 64];   // waves x sets x 4 channel steps x 64 lanes
+  // key metadata blocks of a tile's one or two groups, indexed by the tile's parity
+  constexpr int kAttChunks = kAttBlock / 16;
+  __shared__ uint4 lds_kc[2][2 * kAttChunks];
 
   const int n = g.n;
   const int t_c = it.t_c;
@@ -322,8 +321,6 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   // tile by the scalar unit) plus a 32-bit offset of the lane.  For cache tiles the lane
   // offsets never change; they are computed here once.
   const uint32_t lo_kc = (uint32_t)(krow * kKRow + kslice * 2 * KB);                          // K codes
-  const uint32_t lo_ka = (uint32_t)(((krow >> k_shift) * 3 * kHeadDim + kslice * 16) * 2);   // K a / b / 1024 + z planes
-  const uint32_t lo_kf = (uint32_t)((krow >> k_shift) * 4);                                   // K group flag
   const uint32_t lo_ku = (uint32_t)((krow * kHeadDim + kslice * 16) * 2);                     // row of an uncompressed cache
   const uint32_t lo_vc = (uint32_t)(key_a * kVRow + co * VB);                        // V codes, first row
   const uint32_t lo_vr = (uint32_t)(key_a * kVRow);                                  // start of that V code row
@@ -332,88 +329,82 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
 
   // The loads of tile `tile`'s raw data for this thread.  `tile` may be any tile of the
   // range (a tile past the end is clamped by the caller and simply not decoded).
-  auto load_raw_k = [&](KRaw<KB>& raw, int tile) __attribute__((always_inline)) {
+  auto load_raw_k = [&](KRaw<KB, F32IN>& raw, int tile) __attribute__((always_inline)) {
     typedef typename Hexdec<KB>::type CodeT;
-    const uint8_t *bc, *ba, *bf;               // uniform bases: codes, a[], flag
-    uint32_t oc, oa[6], of;
     if (tile < ntc && compressed) {
-      bc = half + g.lay.k_codes + ((int64_t)h * g.t_cap + tile * kTileK) * kKRow;
-      oc = lo_kc;
-      const int64_t grp = (int64_t)h * g.g_cap + ((tile * kTileK) >> k_shift);
-      ba = half + g.lay.k_att + grp * (3 * kHeadDim * 2);
-      oa[0] = lo_ka; oa[1] = lo_ka + 16;
-      oa[2] = lo_ka + kHeadDim * 2; oa[3] = lo_ka + kHeadDim * 2 + 16;
-      oa[4] = lo_ka + kHeadDim * 4; oa[5] = lo_ka + kHeadDim * 4 + 16;
-      bf = half + g.lay.k_flag + grp * 4;
-      of = lo_kf;
+      const uint8_t* bc = half + g.lay.k_codes + ((int64_t)h * g.t_cap + tile * kTileK) * kKRow;
+      raw.c = *reinterpret_cast<const CodeT*>(bc + lo_kc);
     } else {
+      const uint8_t* ba;
+      uint32_t q0;
       if (tile < ntc) {
         // uncompressed bf16 cache: rows of 64 bf16; every row of a tile is inside the allocation
         ba = half + g.lay.k_codes + ((int64_t)h * g.t_cap + tile * kTileK) * (kHeadDim * 2);
-        oa[0] = lo_ku; oa[1] = lo_ku + 16;
-        oa[2] = oa[3] = oa[0];
+        q0 = lo_ku;
       } else {
         const int trow = (tile - ntc) * kTileK;
         const uint32_t r = (uint32_t)min(krow, n - 1 - trow);          // rows past the frame are zeroed when decoded
         constexpr uint32_t elt = F32IN ? 4 : 2;
         ba = reinterpret_cast<const uint8_t*>(it.k) + ((int64_t)trow * g.tok_stride + (int64_t)h * g.head_stride) * elt;
-        const uint32_t q0 = (r * (uint32_t)g.tok_stride + kslice * 16) * elt;
-        oa[0] = q0; oa[1] = q0 + 16;
-        if constexpr (F32IN) { oa[2] = q0 + 32; oa[3] = q0 + 48; } else { oa[2] = oa[3] = q0; }
+        q0 = (r * (uint32_t)g.tok_stride + kslice * 16) * elt;
       }
-      oa[4] = oa[5] = oa[0];
-      bc = bf = ba;
-      oc = of = oa[0];
-    }
-    raw.c = *reinterpret_cast<const CodeT*>(bc + oc);
-#pragma unroll
-    for (int i = 0; i < 6; ++i) raw.a[i] = *reinterpret_cast<const uint4*>(ba + oa[i]);
-    raw.flag = *reinterpret_cast<const uint32_t*>(bf + of);
-  };
-  auto load_raw_v = [&](VRaw<VB>& raw, int tile) __attribute__((always_inline)) {
-    typedef typename Octet<VB>::type CodeT;
-    const uint8_t *bc, *ba, *bm;               // uniform bases: codes, a[], m
-    uint32_t oc0, oc1, oa0, oa1, oa2, oa3, om0, om1;
-    if (tile < ntc && compressed) {
-      const int64_t row0t = (int64_t)h * g.t_cap + tile * kTileK;
-      bc = half + g.lay.v_codes + row0t * kVRow;
-      oc0 = lo_vc; oc1 = lo_vc + kVRow;
-      bm = half + g.lay.v_meta + row0t * ngv * (int64_t)sizeof(VMeta);
-      om0 = lo_vm; om1 = lo_vm + ngv * (int)sizeof(VMeta);
-      ba = bc; oa0 = oa1 = oa2 = oa3 = lo_vr;
-    } else {
-      if (tile < ntc) {
-        // uncompressed bf16 cache: rows of 64 bf16; the row after a tile's last valid one is in bounds
-        ba = half + g.lay.v_codes + ((int64_t)h * g.t_cap + tile * kTileK) * (kHeadDim * 2);
-        oa0 = lo_un; oa1 = lo_un + kHeadDim * 2;
-        oa2 = oa3 = oa0;
-      } else {
-        const int trow = (tile - ntc) * kTileK;
-        const int lim = n - 1 - trow;                                   // rows past the frame are zeroed when decoded
-        const uint32_t r0 = (uint32_t)min(key_a, lim), r1 = (uint32_t)min(key_a + 1, lim);
-        constexpr uint32_t elt = F32IN ? 4 : 2;
-        ba = reinterpret_cast<const uint8_t*>(it.v) + ((int64_t)trow * g.tok_stride + (int64_t)h * g.head_stride) * elt;
-        const uint32_t ts = (uint32_t)g.tok_stride;
-        const uint32_t q0 = (r0 * ts + co * 8) * elt, q1 = (r1 * ts + co * 8) * elt;
-        if constexpr (F32IN) {
-          oa0 = q0; oa1 = q0 + 16; oa2 = q1; oa3 = q1 + 16;
-        } else {
-          oa0 = q0; oa1 = q1; oa2 = oa3 = q0;
+      raw.a[0] = *reinterpret_cast<const uint4*>(ba + q0);
+      raw.a[1] = *reinterpret_cast<const uint4*>(ba + q0 + 16);
+      if constexpr (F32IN) {
+        if (tile >= ntc) {
+          raw.a[2] = *reinterpret_cast<const uint4*>(ba + q0 + 32);
+          raw.a[3] = *reinterpret_cast<const uint4*>(ba + q0 + 48);
         }
       }
-      bc = bm = ba;
-      oc0 = oc1 = om0 = om1 = oa0;
     }
-    raw.c[0] = *reinterpret_cast<const CodeT*>(bc + oc0);
-    raw.c[1] = *reinterpret_cast<const CodeT*>(bc + oc1);
-    raw.a[0] = *reinterpret_cast<const uint4*>(ba + oa0);
-    raw.a[1] = *reinterpret_cast<const uint4*>(ba + oa1);
-    if constexpr (F32IN) {
-      raw.a[2] = *reinterpret_cast<const uint4*>(ba + oa2);
-      raw.a[3] = *reinterpret_cast<const uint4*>(ba + oa3);
+  };
+  // The metadata blocks of a cached tile's key groups travel global -> one register of 50
+  // lanes of wave 4 -> LDS (the block is the same for all 64 rows of a group, so the key
+  // waves read it from there instead of loading it 64-fold).
+  uint4 kc_reg = make_uint4(0, 0, 0, 0);
+  auto kc_load = [&](int tile) __attribute__((always_inline)) {
+    if (tile < ntc && tile < tile_end && compressed && lane < 2 * kAttChunks) {
+      const int gi = lane >= kAttChunks ? 1 : 0;
+      const int grp = min(((tile * kTileK) >> k_shift) + gi, g.g_cap - 1);
+      kc_reg = *reinterpret_cast<const uint4*>(half + g.lay.k_att + ((int64_t)h * g.g_cap + grp) * kAttBlock + (lane - gi * kAttChunks) * 16);
     }
-    raw.m[0] = *reinterpret_cast<const uint2*>(bm + om0);
-    raw.m[1] = *reinterpret_cast<const uint2*>(bm + om1);
+  };
+  auto kc_store = [&](int tile) __attribute__((always_inline)) {
+    if (lane < 2 * kAttChunks) lds_kc[tile & 1][lane] = kc_reg;
+  };
+  auto load_raw_v = [&](VRaw<VB, F32IN>& raw, int tile) __attribute__((always_inline)) {
+    typedef typename Octet<VB>::type CodeT;
+    if (tile < ntc && compressed) {
+      const int64_t row0t = (int64_t)h * g.t_cap + tile * kTileK;
+      const uint8_t* bc = half + g.lay.v_codes + row0t * kVRow;
+      const uint8_t* bm = half + g.lay.v_meta + row0t * ngv * (int64_t)sizeof(VMeta);
+      raw.c[0] = *reinterpret_cast<const CodeT*>(bc + lo_vc);
+      raw.c[1] = *reinterpret_cast<const CodeT*>(bc + lo_vc + kVRow);
+      raw.m[0] = *reinterpret_cast<const uint2*>(bm + lo_vm);
+      raw.m[1] = *reinterpret_cast<const uint2*>(bm + lo_vm + ngv * (int)sizeof(VMeta));
+    } else if (tile < ntc) {
+      // uncompressed bf16 cache: rows of 64 bf16; the row after a tile's last valid one is in bounds
+      const uint8_t* ba = half + g.lay.v_codes + ((int64_t)h * g.t_cap + tile * kTileK) * (kHeadDim * 2);
+      raw.a[0] = *reinterpret_cast<const uint4*>(ba + lo_un);
+      raw.a[1] = *reinterpret_cast<const uint4*>(ba + lo_un + kHeadDim * 2);
+    } else {
+      const int trow = (tile - ntc) * kTileK;
+      const int lim = n - 1 - trow;                                   // rows past the frame are zeroed when decoded
+      const uint32_t r0 = (uint32_t)min(key_a, lim), r1 = (uint32_t)min(key_a + 1, lim);
+      constexpr uint32_t elt = F32IN ? 4 : 2;
+      const uint8_t* ba = reinterpret_cast<const uint8_t*>(it.v) + ((int64_t)trow * g.tok_stride + (int64_t)h * g.head_stride) * elt;
+      const uint32_t ts = (uint32_t)g.tok_stride;
+      const uint32_t q0 = (r0 * ts + co * 8) * elt, q1 = (r1 * ts + co * 8) * elt;
+      if constexpr (F32IN) {
+        raw.a[0] = *reinterpret_cast<const uint4*>(ba + q0);
+        raw.a[1] = *reinterpret_cast<const uint4*>(ba + q0 + 16);
+        raw.a[2] = *reinterpret_cast<const uint4*>(ba + q1);
+        raw.a[3] = *reinterpret_cast<const uint4*>(ba + q1 + 16);
+      } else {
+        raw.a[0] = *reinterpret_cast<const uint4*>(ba + q0);
+        raw.a[1] = *reinterpret_cast<const uint4*>(ba + q1);
+      }
+    }
   };
 
   // K: the row's sixteen channels as hi and lo, two 16-byte stores each (positions in
@@ -442,17 +433,23 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   };
 
   // De-quantise / convert the raw registers of `tile` into LDS buffer `buf`.
-  auto decode_store_k = [&](const KRaw<KB>& raw, int tile, int buf) __attribute__((always_inline)) {
+  auto decode_store_k = [&](const KRaw<KB, F32IN>& raw, int tile, int buf, bool force_plain) __attribute__((always_inline)) {
     if (tile < ntc && compressed) {
       // rows past the cache's end hold finite stale values; their logits are masked
-      bool plain = KB == 8;
-      if constexpr (KB != 8) plain = __any(raw.flag != 0);
+      bool plain = KB == 8 || force_plain;
+      const uint4* kc = lds_kc[tile & 1] + (krow >> k_shift) * kAttChunks;
+      if constexpr (KB != 8) {
+        if (!force_plain) plain = __any(*reinterpret_cast<const uint32_t*>(kc + 3 * kHeadDim * 2 / 16) != 0);
+      }
       if (!plain) {
         if constexpr (KB != 8) {
           // packed f16: m = (1024 + code) - (1024 + z) exactly, hi = m * a exactly, lo = m * b
-          const uint32_t aw[8] = {raw.a[0].x, raw.a[0].y, raw.a[0].z, raw.a[0].w, raw.a[1].x, raw.a[1].y, raw.a[1].z, raw.a[1].w};
-          const uint32_t bw[8] = {raw.a[2].x, raw.a[2].y, raw.a[2].z, raw.a[2].w, raw.a[3].x, raw.a[3].y, raw.a[3].z, raw.a[3].w};
-          const uint32_t zw[8] = {raw.a[4].x, raw.a[4].y, raw.a[4].z, raw.a[4].w, raw.a[5].x, raw.a[5].y, raw.a[5].z, raw.a[5].w};
+          const uint4 a0 = kc[kslice * 2], a1 = kc[kslice * 2 + 1];
+          const uint4 b0 = kc[8 + kslice * 2], b1 = kc[8 + kslice * 2 + 1];
+          const uint4 z0 = kc[16 + kslice * 2], z1 = kc[16 + kslice * 2 + 1];
+          const uint32_t aw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+          const uint32_t bw[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+          const uint32_t zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
           uint32_t hi[8], lo[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
@@ -508,7 +505,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
       store_k_floats(buf, x);
     }
   };
-  auto decode_store_v = [&](const VRaw<VB>& raw, int tile, int buf) __attribute__((always_inline)) {
+  auto decode_store_v = [&](const VRaw<VB, F32IN>& raw, int tile, int buf) __attribute__((always_inline)) {
     if (tile < ntc && compressed) {
       const int ja = tile * kTileK + key_a;
       const bool full = (tile + 1) * kTileK <= t_c;       // uniform; only a cache's last tile can be ragged
@@ -602,7 +599,11 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
     f32x16 s[2][NB];                               // [key half][query block], log2-domain logits minus m
     // The operands come from LDS a few steps ahead of the MFMAs that use them (a step =
     // one key half of one 16-channel slice: the K hi and lo fragments).
+#ifdef KVX_AHEAD
+    constexpr int kAhead = KVX_AHEAD;
+#else
     constexpr int kAhead = 3;
+#endif
     f16x8 ah[8], al[8], qh[4][NB], ql[4];
     auto read_k = [&](int i) __attribute__((always_inline)) {
       const int ks = i >> 1, mb = i & 1;
@@ -634,8 +635,10 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
       }
     }
     // pin the order: the initial reads, then per step the reads issued for later steps and its MFMAs
+#ifndef KVX_NO_PINS
     sched_group<0x100, 2 * kAhead + 2 * NB + (F32IN ? 2 : 0)>();
     pin_qk_steps<NB, F32IN, kAhead>(std::make_integer_sequence<int, 8>{});
+#endif
     KVX_SETPRIO(0);
     KVX_STAMP();     // QK issued
 
@@ -733,10 +736,12 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[kk][cb], pb[nb][kk], o[cb][nb], 0, 0, 0);
     }
+#ifndef KVX_NO_PINS
     sched_group<0x100, 4>();
     sched_group<0x008, 2 * NB>();
     sched_group<0x100, 4>();
     sched_group<0x008, 6 * NB>();
+#endif
     KVX_SETPRIO(0);
     KVX_STAMP();     // PV issued
   };
@@ -752,21 +757,41 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   // tile's raw data is loaded one interval before it is decoded.
   auto tile_loop = [&](auto rolec) __attribute__((always_inline)) {
     constexpr bool ROLE_K = decltype(rolec)::value;
-    typename std::conditional<ROLE_K, KRaw<KB>, VRaw<VB>>::type raw;
+    typename std::conditional<ROLE_K, KRaw<KB, F32IN>, VRaw<VB, F32IN>>::type raw;
+#ifdef KVX_ABL_NOWAIT
+    typename std::conditional<ROLE_K, KRaw<KB, F32IN>, VRaw<VB, F32IN>>::type raw2;
+    bool inloop = false;
+    auto load_raw = [&](int tile) __attribute__((always_inline)) {
+      if (inloop) { if constexpr (ROLE_K) load_raw_k(raw2, tile); else load_raw_v(raw2, tile); }
+      else { if constexpr (ROLE_K) load_raw_k(raw, tile); else load_raw_v(raw, tile); }
+    };
+#else
     auto load_raw = [&](int tile) __attribute__((always_inline)) {
       if constexpr (ROLE_K) load_raw_k(raw, tile); else load_raw_v(raw, tile);
     };
-    auto decode_store = [&](int tile, int buf) __attribute__((always_inline)) {
-      if constexpr (ROLE_K) decode_store_k(raw, tile, buf); else decode_store_v(raw, tile, buf);
+#endif
+    auto decode_store = [&](int tile, int buf, bool first) __attribute__((always_inline)) {
+      if constexpr (ROLE_K) decode_store_k(raw, tile, buf, first); else decode_store_v(raw, tile, buf);
     };
     const int last = tile_end - 1;
+    const bool kc_wave = !ROLE_K && wave == 4;
 #ifdef KVX_ABL_ZERO
     for (int i = tid; i < 2 * kTileElems; i += blockDim.x) { (&lds_khi[0][0])[i] = 0; (&lds_klo[0][0])[i] = 0; (&lds_v[0][0])[i] = 0; }
 #endif
     load_raw(tile_begin);
+    if (kc_wave) kc_load(tile_begin + 1);
     stage_q();
-    decode_store(tile_begin, 0);
+    // the first key tile is decoded from its scales and zero-points directly: its metadata
+    // blocks would cost a second memory round trip before the first barrier
+    decode_store(tile_begin, 0, true);
+    if (kc_wave) {
+      kc_store(tile_begin + 1);
+      kc_load(tile_begin + 2);
+    }
     load_raw(min(tile_begin + 1, last));
+#ifdef KVX_ABL_NOWAIT
+    inloop = true;
+#endif
     __syncthreads();
     for (int t = tile_begin; t < tile_end; ++t) {
       const int buf = (t - tile_begin) & 1;
@@ -779,7 +804,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
       if constexpr (ROLE_K) {
         run_compute(t, buf);      // 1, 2, 3
 #ifndef KVX_ABL_NODECODE
-        if (more) decode_store(t + 1, buf ^ 1);
+        if (more) decode_store(t + 1, buf ^ 1, false);
 #endif
         KVX_STAMP();     // 4: decoded
 #ifndef KVX_ABL_NOLOAD
@@ -787,12 +812,14 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
 #endif
         KVX_STAMP();     // 5: loads issued
       } else {
+        if (kc_wave) kc_store(t + 2);       // the blocks of tile t + 2, loaded one interval ago
 #ifndef KVX_ABL_NODECODE
-        if (more) decode_store(t + 1, buf ^ 1);
+        if (more) decode_store(t + 1, buf ^ 1, false);
 #endif
         KVX_STAMP();     // 1: decoded
 #ifndef KVX_ABL_NOLOAD
         load_raw(min(t + 2, last));
+        if (kc_wave) kc_load(t + 3);
 #endif
         KVX_STAMP();     // 2: loads issued
         run_compute(t, buf);      // 3, 4, 5
@@ -800,12 +827,10 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
       __syncthreads();
       KVX_STAMP();       // 6: past the barrier
     }
-  };
-#ifdef KVX_ROLE_PRIO
-  // static priorities by role (measurement switch): KVX_ROLE_PRIO = 1: staging waves first, 2: the reverse
-  if (KVX_ROLE_PRIO == 1) { if (wave < 4) __builtin_amdgcn_s_setprio(2); else if (wave < 8) __builtin_amdgcn_s_setprio(1); }
-  else { if (wave >= 8) __builtin_amdgcn_s_setprio(2); else if (wave >= 4) __builtin_amdgcn_s_setprio(1); }
+#ifdef KVX_ABL_NOWAIT
+    if (raw2.c == raw.c && tile_end == 12345) lds_kc[0][lane] = make_uint4(1, 2, 3, 4);
 #endif
+  };
   if (tile_begin < tile_end) {
     if (wave < 4) {
       tile_loop(std::true_type{});

@@ -189,8 +189,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   L.k_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * k_row, 256);
   L.k_scale = off; off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
   L.k_zero = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
-  L.k_att = off;   off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * 3 * kHeadDim * 2), 256);
-  L.k_flag = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * 4), 256);
+  L.k_att = off;   off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kAttBlock), 256);
   L.v_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * v_row, 256);
   L.v_meta = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * (int64_t)sizeof(VMeta)), 256);
   L.ids = off;     off = align_up(off + (int64_t)g.t_cap * 4, 256);
@@ -396,7 +395,7 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
   memset(s, 0, sizeof *s);
   s->bytes_allocated = h->bytes_arena + h->bytes_scratch + h->bytes_part;
   s->bytes_k_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.k_bits / 8);
-  s->bytes_k_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.g_cap * (kHeadDim * 14 + 4));
+  s->bytes_k_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.g_cap * (kHeadDim * 8 + kAttBlock));
   s->bytes_v_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.v_bits / 8);
   s->bytes_v_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * 8);
   s->bytes_ids = nc * halves * (int64_t)g.t_cap * 4;
@@ -423,7 +422,7 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
     s->bytes_live_per_cache = 2 * (int64_t)g.H * T * kHeadDim * 2;
   } else {
     const int64_t groups = (T + g.k_group - 1) / g.k_group;
-    s->bytes_live_per_cache = (int64_t)g.H * T * kHeadDim * g.k_bits / 8 + (int64_t)g.H * groups * (kHeadDim * 14 + 4) +
+    s->bytes_live_per_cache = (int64_t)g.H * T * kHeadDim * g.k_bits / 8 + (int64_t)g.H * groups * (kHeadDim * 8 + kAttBlock) +
                               (int64_t)g.H * T * kHeadDim * g.v_bits / 8 + (int64_t)g.H * T * (kHeadDim / g.v_group) * 8 + T * 4;
   }
   return KV_OK;

@@ -23,8 +23,7 @@ struct CacheLayout {
   int64_t k_codes;    // [H][t_cap][d * k_bits / 8]
   int64_t k_scale;    // [H][g_cap][d] float
   int64_t k_zero;     // [H][g_cap][d] int32
-  int64_t k_att;      // [H][g_cap][3][d] f16: the key metadata in the form the attention kernel consumes (see k_att_pos)
-  int64_t k_flag;     // [H][g_cap] uint32: nonzero if a channel of the group cannot take the packed f16 path
+  int64_t k_att;      // [H][g_cap][kAttBlock bytes]: the key metadata in the form the attention kernel consumes (see below)
   int64_t v_codes;    // [H][t_cap][d * v_bits / 8]
   int64_t v_meta;     // [H][t_cap][d / v_group] VMeta
   int64_t ids;        // [t_cap] int32
@@ -100,9 +99,13 @@ struct KvxBatch {
 // sk = s * (softmax scale * log2 e) split as sk = a + b, a = the top kAttSplitBits
 // significant bits of sk, the product m * a is exact in f16 and m * b is a small correction,
 // so the attention kernel forms the key as an f16 pair (m * a, m * b) with packed f16
-// arithmetic.  Per (head, group, channel) the planes hold a, b and 1024 + z as f16.  The
-// channels of a plane are stored in the order the attention kernel keeps them in LDS:
-// codes that sit 16 bits apart in a code word become the two halves of one packed value.
+// arithmetic.  Per (head, group) a block of kAttBlock bytes holds three planes of 64 f16
+// (a, b and 1024 + z per channel) and a 16-byte tail whose first word is nonzero if some
+// channel of the group cannot take that path (zero-point out of range, scale outside f16's
+// normal range).  The channels of a plane are stored in the order the attention kernel
+// keeps them in LDS: codes that sit 16 bits apart in a code word become the two halves of
+// one packed value.
+constexpr int kAttBlock = 3 * kHeadDim * 2 + 16;
 constexpr int kAttSplitBits = 6;          // significant bits of a: |m| < 32 keeps m * a within f16's 11
 constexpr int kAttZMin = -16, kAttZMax = 31;
 // position (0..15) of channel i (0..15) of a 16-channel slice in the stored order
