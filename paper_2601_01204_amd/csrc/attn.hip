@@ -4,26 +4,20 @@
 // Work decomposition: a workgroup owns a tile of up to 12 32-row query blocks of one head
 // (the frame's blocks cut evenly over tiles), one block per wave, so 8 to 12 waves, and a
 // contiguous range of 64-key tiles (split-KV).  Per tile waves 0-3 de-quantise the K
-// codes (a lane owns a key row, a wave a 16-channel slice) and waves 4-7 the V codes once
-// into LDS (K row-major, V transposed), then every
+// codes and waves 4-7 the V codes once into LDS (K row-major, V transposed), then every
 // wave runs S^T = K Q^T and O^T += V^T P^T on the matrix cores with an online softmax in
 // registers.  Computing the transposed products puts a query in a lane and its keys in
 // that lane's registers, so the probabilities feed the second MFMA straight from
 // registers (the key order inside a 16-key step is a permutation shared by V^T's LDS
 // layout) and the row statistics stay in the lane.
 //
-// Precision.  A de-quantised key s * (code - z) is an fp32 value; rounding it to the 11
-// significant bits of f16 perturbs the logits of the dominant key channels by more than the
-// output tolerance allows.  K~ is therefore held as an f16 pair hi + lo and S^T takes two f16
-// MFMAs (v_mfma_f32_32x32x16_f16) against the queries, which are bf16 inputs converted to
-// f16 without loss.  For cached keys the pair is formed without any fp32 arithmetic: with
-// m = code - z a small integer and the scale (times the softmax scale) split as a + b, a =
-// its top six significant bits, m * a is exact in f16 and m * b is the correction; a, b and
-// 1024 + z come precomputed as f16 from the cache (written when a key group is quantised)
-// and the codes enter as the f16 numbers 1024 + code by OR-ing them into a constant.  A group
-// whose zero-point lies outside [-16, 31] (or 8-bit codes) takes a plain fp32 path.  P and V~
-// go through the same f16 MFMA; a cached value is the f16 product of (code - z), exact, and
-// its scale rounded to f16.  fp32 inputs are split into f16 pairs (queries too).
+// Precision.  A de-quantised key s * (code - z) is an fp32 value; rounding it to 8
+// significand bits perturbs the logits of the dominant key channels by ~1e-2, far above
+// the output tolerance.  K~ is therefore held as a bf16 pair hi + lo (hi = truncation,
+// lo = truncated remainder, together 16 significand bits) and S^T takes two bf16 MFMAs
+// (v_mfma_f32_32x32x16_bf16) against the exact bf16 queries.  P and V~ go through the
+// f16 MFMA (v_mfma_f32_32x32x16_f16, 11 significand bits, same rate).  fp32 inputs are
+// split the same way (queries too).
 //
 // Softmax.  The softmax scale times log2(e) is folded into the keys as they are staged,
 // so S^T is already in log2 units.  Each query keeps a reference m and p = 2^(s - m) is
@@ -32,16 +26,13 @@
 // wave-uniform branch) is m raised for every row whose largest key exceeds it by more
 // than kRescaleGap, O and l are rescaled and the tile's probabilities are formed again.
 //
-// Schedule.  A wave issues in order, and its LDS operand reads, MFMAs and vector
-// instructions overlap little with each other (measured on gfx950: interleaving the three
-// kinds inside one wave gains a few per cent at most, because every 16-byte LDS read holds
-// the wave for about as long as it holds the LDS return path), so the overlap has to come
-// from different waves of a SIMD being in different phases.  A SIMD holds up to three waves
-// of the workgroup (w, w + 4, w + 8), each with the same matrix work; waves 0-3 compute a
-// tile and then stage K of the next one, waves 4-7 stage V first and then compute, waves
-// 8-11 only compute, so their MFMA and vector stretches fall at different times between two
-// barriers.  What the staging waves execute per tile comes straight off the attention
-// rate, hence the packed f16 de-quantisation above.
+// Schedule.  Measured on gfx950, an MFMA overlaps only one or two vector instructions of
+// its own wave and about a quarter of its cycles with vector work of other waves, so a
+// SIMD is close to a serial resource and what matters is that it always has a wave that
+// can issue.  A SIMD holds up to three waves of the workgroup (w, w + 4, w + 8), each
+// with the same matrix work; waves 0-3 compute a tile and then stage K of the next one,
+// waves 4-7 stage V first and then compute, waves 8-11 only compute, so their MFMA and
+// vector stretches fall at different times between two barriers.
 #include "kvx_dev.h"
 
 #include <type_traits>
@@ -49,9 +40,10 @@
 
 namespace kvx {
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -61,15 +53,8 @@ constexpr float kNegBig = -1.0e30f;
 constexpr float kRescaleGap = 8.0f;               // log2 units
 constexpr int kAttnMaxWaves = 12;                 // waves (= 32-row query blocks) per workgroup, three per SIMD
 constexpr float kSumLimit = 1.0e37f;              // a row sum at or above this (or NaN) saw an f16 overflow
-constexpr uint32_t kMagic = 0x64006400u;          // two f16 values 1024: OR-ing an integer below 1024 into a half adds it
-constexpr int kVZLimit = 60;                      // value zero-points beyond this take the plain path
 
 #define KVX_FENCE() __builtin_amdgcn_sched_barrier(0)
-#ifdef KVX_USE_SETPRIO
-#define KVX_SETPRIO(x) __builtin_amdgcn_s_setprio(x)
-#else
-#define KVX_SETPRIO(x)
-#endif
 
 __device__ __forceinline__ int swap23(int x) { return (x & ~0xC) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
@@ -82,32 +67,31 @@ __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
   const f32x2 x = {a, b};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
 }
-// Two fp32 values -> packed f16 roundings (hi) and packed f16 roundings of the remainders (lo).
-__device__ __forceinline__ void split_f16(float a, float b, uint32_t& hi, uint32_t& lo) {
-  hi = pack_f16(a, b);
-  const f16x2 h = __builtin_bit_cast(f16x2, hi);
-  lo = pack_f16(a - (float)h[0], b - (float)h[1]);
+// Two fp32 values -> packed bf16 truncations (hi) and packed bf16 truncated remainders (lo).
+__device__ __forceinline__ void split_bf16(float a, float b, uint32_t& hi, uint32_t& lo) {
+  const uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+  hi = __builtin_amdgcn_perm(ub, ua, 0x07060302u);          // the upper halves of a (low) and b (high)
+  const float ra = a - __uint_as_float(ua & 0xFFFF0000u), rb = b - __uint_as_float(ub & 0xFFFF0000u);
+  lo = __builtin_amdgcn_perm(__float_as_uint(rb), __float_as_uint(ra), 0x07060302u);
 }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-__device__ __forceinline__ uint32_t pk_sub(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, a) - __builtin_bit_cast(f16x2, b));
-}
-__device__ __forceinline__ uint32_t pk_mul(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, a) * __builtin_bit_cast(f16x2, b));
-}
 
-// The codes of eight consecutive channels of one row (value role): 2, 4 or 8 bytes.
+// The codes of eight consecutive channels of one row: 2, 4 or 8 bytes.
 template <int B> struct Octet;
 template <> struct Octet<2> { typedef uint16_t type; };
 template <> struct Octet<4> { typedef uint32_t type; };
 template <> struct Octet<8> { typedef uint2 type; };
-// The codes of sixteen consecutive channels of one row (key role): 4, 8 or 16 bytes.
-template <int B> struct Hexdec;
-template <> struct Hexdec<2> { typedef uint32_t type; };
-template <> struct Hexdec<4> { typedef uint2 type; };
-template <> struct Hexdec<8> { typedef uint4 type; };
 
+template <int B>
+__device__ __forceinline__ int octet_code(const typename Octet<B>::type& w, int e) {
+  if constexpr (B == 4) return (int)((w >> (4 * e)) & 0xFu);
+  else if constexpr (B == 2) return (int)(((uint32_t)w >> (2 * e)) & 0x3u);
+  else return (int)(((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xFFu);
+}
+
+// The same eight codes as floats.  Bytes convert in one instruction each, so 4-bit codes
+// are first spread into the bytes of two words (even and odd channels).
 // Byte K of a word as a float (v_cvt_f32_ubyteK; written out because the compiler would
 // otherwise merge the nibble masks below back into one bit-field extract per value).
 template <int K>
@@ -119,8 +103,6 @@ __device__ __forceinline__ float byte_to_float(uint32_t w) {
   else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(f) : "v"(w));
   return f;
 }
-// Eight codes as floats.  Bytes convert in one instruction each, so 4-bit codes are first
-// spread into the bytes of two words (even and odd channels).
 template <int B>
 __device__ __forceinline__ void octet_floats(const typename Octet<B>::type& w, float (&f)[8]) {
   if constexpr (B == 8) {
@@ -135,44 +117,19 @@ __device__ __forceinline__ void octet_floats(const typename Octet<B>::type& w, f
     for (int e = 0; e < 8; ++e) f[e] = (float)(((uint32_t)w >> (2 * e)) & 0x3u);
   }
 }
-// Code of channel e (0..15) of a sixteen-channel word.
-template <int B>
-__device__ __forceinline__ int hexdec_code(const typename Hexdec<B>::type& w, int e) {
-  if constexpr (B == 2) return (int)((w >> (2 * e)) & 0x3u);
-  else if constexpr (B == 4) return (int)(((e < 8 ? w.x : w.y) >> (4 * (e & 7))) & 0xFu);
-  else {
-    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-    return (int)((ww[e >> 2] >> (8 * (e & 3))) & 0xFFu);
-  }
-}
 
-// Sixteen channel values of a slice, natural order -> stored order (indices are template
-// constants, so the arrays stay in registers).
-template <int B, int... P>
-__device__ __forceinline__ void to_stored_order(const float (&x)[16], float (&y)[16], std::integer_sequence<int, P...>) {
-  ((y[P] = x[k_att_chan<B>(P)]), ...);
-}
+// Staging registers of one thread: two rows x eight channels of K (waves 0-3) or of V
+// (waves 4-7) as loaded, before decoding.  Every tile fills the same registers with the
+// same straight-line sequence of loads, whatever the tile holds (only the addresses are
+// selected), so the loads of a later tile stay in flight across the barriers.
+//   cached K tile : c = the two rows' codes, a[0..1] = the channels' scales, a[2..3] = zero-points
+//   cached V tile : c = codes, m = the two rows' (scale, zero-point)
+//   bf16 rows     : a[0], a[1] = the two rows (own frame, uncompressed cache)
+//   fp32 rows     : a[0..1] = first row, a[2..3] = second row (own frame)
+// Registers a tile does not use are loaded from a valid dummy address.
 template <int B>
-__device__ __forceinline__ void to_stored_order(const float (&x)[16], float (&y)[16]) {
-  to_stored_order<B>(x, y, std::make_integer_sequence<int, 16>{});
-}
-
-// Staging registers of one thread as loaded, before decoding.  A tile's raw data is loaded
-// one barrier interval before it is decoded and stays in flight across the barrier.
-// Key role: one key row x sixteen channels.
-//   cached tile : c = the codes (the group's metadata block reaches the key waves through LDS)
-//   bf16 row    : a[0..1] (own frame, uncompressed cache);  fp32 row: a[0..3] (own frame)
-template <int B, bool F32>
-struct KRaw {
-  uint4 a[F32 ? 4 : 2];
-  typename Hexdec<B>::type c;
-};
-// Value role: two key rows x eight channels.
-//   cached tile : c = the two rows' codes, m = the two rows' (scale, zero-point)
-//   bf16 rows   : a[0], a[1] = the two rows;  fp32 rows: a[0..1] = first row, a[2..3] = second row
-template <int B, bool F32>
-struct VRaw {
-  uint4 a[F32 ? 4 : 2];
+struct TileRaw {
+  uint4 a[4];
   typename Octet<B>::type c[2];
   uint2 m[2];
 };
@@ -208,16 +165,11 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   const int l32 = lane & 31;
   const int hf = lane >> 5;
 
-  // K tiles hold, per key row, the 64 channels in stored order: inside every 16-channel
-  // slice position p holds channel k_att_chan<KB>(p); the query fragments use the same order.
   __shared__ __attribute__((aligned(16))) uint16_t lds_khi[2][kTileElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_klo[2][kTileElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileElems];
   constexpr int kQSets = F32IN ? 2 : 1;                   // bf16 queries: one fragment set; fp32: hi and lo
   __shared__ uint4 lds_q[kAttnMaxWaves * kQSets * 4 * 64];   // waves x sets x 4 channel steps x 64 lanes
-  // key metadata blocks of a tile's one or two groups, indexed by the tile's parity
-  constexpr int kAttChunks = kAttBlock / 16;
-  __shared__ uint4 lds_kc[2][2 * kAttChunks];
 
   const int n = g.n;
   const int t_c = it.t_c;
@@ -240,47 +192,39 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   // ---- this wave's query fragments (B operand of S^T = K Q^T) ---------------------
   // They live in a private LDS region of the wave, one 16-byte entry per lane and
   // 16-channel step (fp32 input: a second set for the lo parts), and are re-read every
-  // tile: the registers they would occupy hold the -m block below instead.  A lane holds
-  // stored positions [8 hf, 8 hf + 8) of each slice of its query row, as f16 (a bf16 input
-  // converts without loss).  They are loaded together with the first tile's raw data, so
-  // that the two global latencies overlap (rows past the frame repeat its last row; their
-  // output is not stored).
+  // tile: the registers they would occupy hold the -m block below instead.
+  // They are loaded together with the first tile's raw data, so that the two global
+  // latencies overlap (rows past the frame repeat its last row; their output is not stored).
   uint4* qbase = lds_q + (wave * kQSets * 4) * 64 + lane;
   auto stage_q = [&]() __attribute__((always_inline)) {
     if (!nblk) return;
     const int qi = min(row0 + l32, n - 1);
     const uint8_t* qrow = reinterpret_cast<const uint8_t*>(it.q) +
-                          ((int64_t)qi * g.tok_stride + (int64_t)h * g.head_stride) * (F32IN ? 4 : 2);
+                          ((int64_t)qi * g.tok_stride + (int64_t)h * g.head_stride + hf * 8) * (F32IN ? 4 : 2);
+    if constexpr (F32IN) {
+      uint4 a[4], c[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      float x[16];                                  // the slice's sixteen channels
-      if constexpr (F32IN) {
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-          const float4 t = *reinterpret_cast<const float4*>(qrow + ks * 64 + v4 * 16);
-          x[4 * v4] = t.x; x[4 * v4 + 1] = t.y; x[4 * v4 + 2] = t.z; x[4 * v4 + 3] = t.w;
-        }
-      } else {
-#pragma unroll
-        for (int v4 = 0; v4 < 2; ++v4) {
-          const uint4 t = *reinterpret_cast<const uint4*>(qrow + ks * 32 + v4 * 16);
-          const uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { x[8 * v4 + 2 * e] = bf16lo_to_f32(w[e]); x[8 * v4 + 2 * e + 1] = bf16hi_to_f32(w[e]); }
-        }
+      for (int ks = 0; ks < 4; ++ks) {
+        a[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 64);
+        c[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 64 + 16);
       }
-      float xs[16], y[8];                           // stored order; this lane's eight positions
-      to_stored_order<KB>(x, xs);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) y[i] = hf ? xs[8 + i] : xs[i];
-      uint32_t hi[4], lo[4];
+      for (int ks = 0; ks < 4; ++ks) {
+        const float x[8] = {__uint_as_float(a[ks].x), __uint_as_float(a[ks].y), __uint_as_float(a[ks].z), __uint_as_float(a[ks].w),
+                            __uint_as_float(c[ks].x), __uint_as_float(c[ks].y), __uint_as_float(c[ks].z), __uint_as_float(c[ks].w)};
+        uint32_t hi[4], lo[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if constexpr (F32IN) split_f16(y[2 * e], y[2 * e + 1], hi[e], lo[e]);
-        else hi[e] = pack_f16(y[2 * e], y[2 * e + 1]);
+        for (int e = 0; e < 4; ++e) split_bf16(x[2 * e], x[2 * e + 1], hi[e], lo[e]);
+        qbase[(0 * 4 + ks) * 64] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        qbase[(1 * 4 + ks) * 64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
       }
-      qbase[(0 * 4 + ks) * 64] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-      if constexpr (F32IN) qbase[(1 * 4 + ks) * 64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    } else {
+      const uint4 q0 = *reinterpret_cast<const uint4*>(qrow), q1 = *reinterpret_cast<const uint4*>(qrow + 32);
+      const uint4 q2 = *reinterpret_cast<const uint4*>(qrow + 64), q3 = *reinterpret_cast<const uint4*>(qrow + 96);
+      qbase[0 * 64] = q0;
+      qbase[1 * 64] = q1;
+      qbase[2 * 64] = q2;
+      qbase[3 * 64] = q3;
     }
   };
 
@@ -302,10 +246,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
       for (int r = 0; r < 16; ++r) o[cb][nb][r] = 0.f;
   }
 
-  // staging roles.  Key role (waves 0-3): key row `lane` of the tile, channels [16 wave,
-  // 16 wave + 16).  Value role (waves 4-7): rows (key_a, key_a + 1), channels [8 co, 8 co + 8).
-  const int krow = lane;
-  const int kslice = wave & 3;
+  // staging role of this thread: rows (key_a, key_a + 1) of the tile, channels [8 co, 8 co + 8)
   const int st = tid & 255;
   const int kp = st & 31;
   const int co = st >> 5;
@@ -320,112 +261,84 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   // Every raw load is addressed as a workgroup-uniform base (scalar registers, advanced per
   // tile by the scalar unit) plus a 32-bit offset of the lane.  For cache tiles the lane
   // offsets never change; they are computed here once.
-  const uint32_t lo_kc = (uint32_t)(krow * kKRow + kslice * 2 * KB);                          // K codes
-  const uint32_t lo_ku = (uint32_t)((krow * kHeadDim + kslice * 16) * 2);                     // row of an uncompressed cache
+  const uint32_t lo_kc = (uint32_t)(key_a * kKRow + co * KB);                        // K codes, first row
+  const uint32_t lo_km = (uint32_t)((((key_a >> k_shift) * kHeadDim) + co * 8) * 4);  // K scales / zero-points
   const uint32_t lo_vc = (uint32_t)(key_a * kVRow + co * VB);                        // V codes, first row
   const uint32_t lo_vr = (uint32_t)(key_a * kVRow);                                  // start of that V code row
   const uint32_t lo_vm = (uint32_t)((key_a * ngv + ((co * 8) >> v_shift)) * (int)sizeof(VMeta));
-  const uint32_t lo_un = (uint32_t)((key_a * kHeadDim + co * 8) * 2);                // rows of an uncompressed cache
+  const uint32_t lo_un = (uint32_t)((key_a * kHeadDim + co * 8) * 2);                // row of an uncompressed cache
 
   // The loads of tile `tile`'s raw data for this thread.  `tile` may be any tile of the
   // range (a tile past the end is clamped by the caller and simply not decoded).
-  auto load_raw_k = [&](KRaw<KB, F32IN>& raw, int tile) __attribute__((always_inline)) {
-    typedef typename Hexdec<KB>::type CodeT;
-    if (tile < ntc && compressed) {
-      const uint8_t* bc = half + g.lay.k_codes + ((int64_t)h * g.t_cap + tile * kTileK) * kKRow;
-      raw.c = *reinterpret_cast<const CodeT*>(bc + lo_kc);
-    } else {
-      const uint8_t* ba;
-      uint32_t q0;
-      if (tile < ntc) {
-        // uncompressed bf16 cache: rows of 64 bf16; every row of a tile is inside the allocation
-        ba = half + g.lay.k_codes + ((int64_t)h * g.t_cap + tile * kTileK) * (kHeadDim * 2);
-        q0 = lo_ku;
-      } else {
-        const int trow = (tile - ntc) * kTileK;
-        const uint32_t r = (uint32_t)min(krow, n - 1 - trow);          // rows past the frame are zeroed when decoded
-        constexpr uint32_t elt = F32IN ? 4 : 2;
-        ba = reinterpret_cast<const uint8_t*>(it.k) + ((int64_t)trow * g.tok_stride + (int64_t)h * g.head_stride) * elt;
-        q0 = (r * (uint32_t)g.tok_stride + kslice * 16) * elt;
-      }
-      raw.a[0] = *reinterpret_cast<const uint4*>(ba + q0);
-      raw.a[1] = *reinterpret_cast<const uint4*>(ba + q0 + 16);
-      if constexpr (F32IN) {
-        if (tile >= ntc) {
-          raw.a[2] = *reinterpret_cast<const uint4*>(ba + q0 + 32);
-          raw.a[3] = *reinterpret_cast<const uint4*>(ba + q0 + 48);
-        }
-      }
-    }
-  };
-  // The metadata blocks of a cached tile's key groups travel global -> one register of 50
-  // lanes of wave 4 -> LDS (the block is the same for all 64 rows of a group, so the key
-  // waves read it from there instead of loading it 64-fold).
-  uint4 kc_reg = make_uint4(0, 0, 0, 0);
-  auto kc_load = [&](int tile) __attribute__((always_inline)) {
-    if (tile < ntc && tile < tile_end && compressed && lane < 2 * kAttChunks) {
-      const int gi = lane >= kAttChunks ? 1 : 0;
-      const int grp = min(((tile * kTileK) >> k_shift) + gi, g.g_cap - 1);
-      kc_reg = *reinterpret_cast<const uint4*>(half + g.lay.k_att + ((int64_t)h * g.g_cap + grp) * kAttBlock + (lane - gi * kAttChunks) * 16);
-    }
-  };
-  auto kc_store = [&](int tile) __attribute__((always_inline)) {
-    if (lane < 2 * kAttChunks) lds_kc[tile & 1][lane] = kc_reg;
-  };
-  auto load_raw_v = [&](VRaw<VB, F32IN>& raw, int tile) __attribute__((always_inline)) {
-    typedef typename Octet<VB>::type CodeT;
+  auto load_raw = [&](auto rolec, auto& raw, int tile) __attribute__((always_inline)) {
+    constexpr bool ROLE_K = decltype(rolec)::value;
+    constexpr int B = ROLE_K ? KB : VB;
+    typedef typename Octet<B>::type CodeT;
+    const uint8_t *bc, *ba, *bz, *bm;          // uniform bases: codes, a[0..1], a[2..3], m
+    uint32_t oc0, oc1, oa0, oa1, oa2, oa3, om0, om1;
     if (tile < ntc && compressed) {
       const int64_t row0t = (int64_t)h * g.t_cap + tile * kTileK;
-      const uint8_t* bc = half + g.lay.v_codes + row0t * kVRow;
-      const uint8_t* bm = half + g.lay.v_meta + row0t * ngv * (int64_t)sizeof(VMeta);
-      raw.c[0] = *reinterpret_cast<const CodeT*>(bc + lo_vc);
-      raw.c[1] = *reinterpret_cast<const CodeT*>(bc + lo_vc + kVRow);
-      raw.m[0] = *reinterpret_cast<const uint2*>(bm + lo_vm);
-      raw.m[1] = *reinterpret_cast<const uint2*>(bm + lo_vm + ngv * (int)sizeof(VMeta));
-    } else if (tile < ntc) {
-      // uncompressed bf16 cache: rows of 64 bf16; the row after a tile's last valid one is in bounds
-      const uint8_t* ba = half + g.lay.v_codes + ((int64_t)h * g.t_cap + tile * kTileK) * (kHeadDim * 2);
-      raw.a[0] = *reinterpret_cast<const uint4*>(ba + lo_un);
-      raw.a[1] = *reinterpret_cast<const uint4*>(ba + lo_un + kHeadDim * 2);
-    } else {
-      const int trow = (tile - ntc) * kTileK;
-      const int lim = n - 1 - trow;                                   // rows past the frame are zeroed when decoded
-      const uint32_t r0 = (uint32_t)min(key_a, lim), r1 = (uint32_t)min(key_a + 1, lim);
-      constexpr uint32_t elt = F32IN ? 4 : 2;
-      const uint8_t* ba = reinterpret_cast<const uint8_t*>(it.v) + ((int64_t)trow * g.tok_stride + (int64_t)h * g.head_stride) * elt;
-      const uint32_t ts = (uint32_t)g.tok_stride;
-      const uint32_t q0 = (r0 * ts + co * 8) * elt, q1 = (r1 * ts + co * 8) * elt;
-      if constexpr (F32IN) {
-        raw.a[0] = *reinterpret_cast<const uint4*>(ba + q0);
-        raw.a[1] = *reinterpret_cast<const uint4*>(ba + q0 + 16);
-        raw.a[2] = *reinterpret_cast<const uint4*>(ba + q1);
-        raw.a[3] = *reinterpret_cast<const uint4*>(ba + q1 + 16);
+      if constexpr (ROLE_K) {
+        bc = half + g.lay.k_codes + row0t * kKRow;
+        oc0 = lo_kc; oc1 = lo_kc + kKRow;
+        const int64_t moff = ((int64_t)h * g.g_cap + ((tile * kTileK) >> k_shift)) * (kHeadDim * 4);
+        ba = half + g.lay.k_scale + moff;
+        bz = half + g.lay.k_zero + moff;
+        oa0 = lo_km; oa1 = lo_km + 16; oa2 = lo_km; oa3 = lo_km + 16;
+        bm = ba; om0 = om1 = lo_km;
       } else {
-        raw.a[0] = *reinterpret_cast<const uint4*>(ba + q0);
-        raw.a[1] = *reinterpret_cast<const uint4*>(ba + q1);
+        bc = half + g.lay.v_codes + row0t * kVRow;
+        oc0 = lo_vc; oc1 = lo_vc + kVRow;
+        bm = half + g.lay.v_meta + row0t * ngv * (int64_t)sizeof(VMeta);
+        om0 = lo_vm; om1 = lo_vm + ngv * (int)sizeof(VMeta);
+        ba = bz = bc; oa0 = oa1 = oa2 = oa3 = lo_vr;
       }
+    } else {
+      if (tile < ntc) {
+        // uncompressed bf16 cache: rows of 64 bf16; the row after a tile's last valid one is in bounds
+        ba = half + (ROLE_K ? g.lay.k_codes : g.lay.v_codes) + ((int64_t)h * g.t_cap + tile * kTileK) * (kHeadDim * 2);
+        oa0 = lo_un; oa1 = lo_un + kHeadDim * 2;
+        oa2 = oa3 = oa0;
+      } else {
+        const int trow = (tile - ntc) * kTileK;
+        const int lim = n - 1 - trow;                                   // rows past the frame are zeroed when decoded
+        const uint32_t r0 = (uint32_t)min(key_a, lim), r1 = (uint32_t)min(key_a + 1, lim);
+        constexpr uint32_t elt = F32IN ? 4 : 2;
+        ba = reinterpret_cast<const uint8_t*>(ROLE_K ? it.k : it.v) + ((int64_t)trow * g.tok_stride + (int64_t)h * g.head_stride) * elt;
+        const uint32_t ts = (uint32_t)g.tok_stride;
+        const uint32_t q0 = (r0 * ts + co * 8) * elt, q1 = (r1 * ts + co * 8) * elt;
+        if constexpr (F32IN) {
+          oa0 = q0; oa1 = q0 + 16; oa2 = q1; oa3 = q1 + 16;
+        } else {
+          oa0 = q0; oa1 = q1; oa2 = oa3 = q0;
+        }
+      }
+      bz = bc = bm = ba;
+      oc0 = oc1 = om0 = om1 = oa0;
+    }
+    raw.c[0] = *reinterpret_cast<const CodeT*>(bc + oc0);
+    raw.c[1] = *reinterpret_cast<const CodeT*>(bc + oc1);
+    raw.a[0] = *reinterpret_cast<const uint4*>(ba + oa0);
+    raw.a[1] = *reinterpret_cast<const uint4*>(ba + oa1);
+    if constexpr (ROLE_K || F32IN) {
+      raw.a[2] = *reinterpret_cast<const uint4*>(bz + oa2);
+      raw.a[3] = *reinterpret_cast<const uint4*>(bz + oa3);
+    }
+    if constexpr (!ROLE_K) {
+      raw.m[0] = *reinterpret_cast<const uint2*>(bm + om0);
+      raw.m[1] = *reinterpret_cast<const uint2*>(bm + om1);
     }
   };
 
-  // K: the row's sixteen channels as hi and lo, two 16-byte stores each (positions in
-  // stored order).  V: rows are channels; the two keys land side by side as one 4-byte
-  // store per channel.
-  auto store_k_words = [&](int buf, const uint32_t (&hi)[8], const uint32_t (&lo)[8]) {
-    uint16_t* ph = lds_khi[buf] + krow * kLdsRow + kslice * 16;
-    uint16_t* pl = lds_klo[buf] + krow * kLdsRow + kslice * 16;
-    *reinterpret_cast<uint4*>(ph) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    *reinterpret_cast<uint4*>(ph + 8) = make_uint4(hi[4], hi[5], hi[6], hi[7]);
-    *reinterpret_cast<uint4*>(pl) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    *reinterpret_cast<uint4*>(pl + 8) = make_uint4(lo[4], lo[5], lo[6], lo[7]);
-  };
-  // sixteen fp32 channel values (natural order, softmax scale applied) -> stored order f16 pairs
-  auto store_k_floats = [&](int buf, const float (&x)[16]) {
-    uint32_t hi[8], lo[8];
-    float y[16];
-    to_stored_order<KB>(x, y);
+  // K: row (key_a + i) gets 8 channels of hi and lo as one 16-byte store each; the values
+  // carry the softmax scale.  V: rows are channels; the two keys land side by side as one
+  // 4-byte store per channel.
+  auto store_k_split = [&](int buf, int i, const float (&x)[8]) {
+    uint32_t hi[4], lo[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) split_f16(y[2 * e], y[2 * e + 1], hi[e], lo[e]);
-    store_k_words(buf, hi, lo);
+    for (int e = 0; e < 4; ++e) split_bf16(x[2 * e], x[2 * e + 1], hi[e], lo[e]);
+    *reinterpret_cast<uint4*>(lds_khi[buf] + (key_a + i) * kLdsRow + co * 8) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    *reinterpret_cast<uint4*>(lds_klo[buf] + (key_a + i) * kLdsRow + co * 8) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
   };
   auto store_v_pair = [&](int buf, const float (&a)[8], const float (&c)[8]) {
 #pragma unroll
@@ -433,110 +346,36 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   };
 
   // De-quantise / convert the raw registers of `tile` into LDS buffer `buf`.
-  auto decode_store_k = [&](const KRaw<KB, F32IN>& raw, int tile, int buf, bool force_plain) __attribute__((always_inline)) {
+  auto decode_store = [&](auto rolec, const auto& raw, int tile, int buf) __attribute__((always_inline)) {
+    constexpr bool ROLE_K = decltype(rolec)::value;
     if (tile < ntc && compressed) {
-      // rows past the cache's end hold finite stale values; their logits are masked
-      bool plain = KB == 8 || force_plain;
-      const uint4* kc = lds_kc[tile & 1] + (krow >> k_shift) * kAttChunks;
-      if constexpr (KB != 8) {
-        if (!force_plain) plain = __any(*reinterpret_cast<const uint32_t*>(kc + 3 * kHeadDim * 2 / 16) != 0);
-      }
-      if (!plain) {
-        if constexpr (KB != 8) {
-          // packed f16: m = (1024 + code) - (1024 + z) exactly, hi = m * a exactly, lo = m * b
-          const uint4 a0 = kc[kslice * 2], a1 = kc[kslice * 2 + 1];
-          const uint4 b0 = kc[8 + kslice * 2], b1 = kc[8 + kslice * 2 + 1];
-          const uint4 z0 = kc[16 + kslice * 2], z1 = kc[16 + kslice * 2 + 1];
-          const uint32_t aw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-          const uint32_t bw[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-          const uint32_t zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
-          uint32_t hi[8], lo[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            uint32_t pr;                       // codes of stored positions 2e, 2e + 1 in the two halves
-            if constexpr (KB == 4) pr = ((e < 4 ? raw.c.x : raw.c.y) >> (4 * (e & 3))) & 0x000F000Fu;
-            else pr = (raw.c >> (2 * e)) & 0x00030003u;
-            const uint32_t m = pk_sub(pr | kMagic, zw[e]);
-            hi[e] = pk_mul(m, aw[e]);
-            lo[e] = pk_mul(m, bw[e]);
-          }
-          store_k_words(buf, hi, lo);
-        }
-      } else {
-        // plain path: Eq. 10 in fp32 from the group's scale and zero-point (loaded here: rare)
-        const int64_t moff = ((int64_t)h * g.g_cap + ((tile * kTileK + krow) >> k_shift)) * kHeadDim + kslice * 16;
-        const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(half + g.lay.k_scale) + moff);
-        const int4* zp = reinterpret_cast<const int4*>(reinterpret_cast<const int32_t*>(half + g.lay.k_zero) + moff);
-        float x[16];
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-          const float4 sv = sp[v4];
-          const int4 zv = zp[v4];
-          const float sa[4] = {sv.x, sv.y, sv.z, sv.w};
-          const int za[4] = {zv.x, zv.y, zv.z, zv.w};
-#pragma unroll
-          for (int k = 0; k < 4; ++k) x[4 * v4 + k] = (sa[k] * sc) * (float)(hexdec_code<KB>(raw.c, 4 * v4 + k) - za[k]);
-        }
-        store_k_floats(buf, x);
-      }
-    } else {
-      int base_row, limit;
-      if (tile < ntc) { base_row = tile * kTileK; limit = t_c; } else { base_row = (tile - ntc) * kTileK; limit = n; }
-      const bool ok = base_row + krow < limit;
-      float x[16];
-      if (F32IN && tile >= ntc) {
-        if constexpr (F32IN) {
-#pragma unroll
-          for (int v4 = 0; v4 < 4; ++v4) {
-            x[4 * v4] = __uint_as_float(raw.a[v4].x); x[4 * v4 + 1] = __uint_as_float(raw.a[v4].y);
-            x[4 * v4 + 2] = __uint_as_float(raw.a[v4].z); x[4 * v4 + 3] = __uint_as_float(raw.a[v4].w);
-          }
-        }
-      } else {
-#pragma unroll
-        for (int v4 = 0; v4 < 2; ++v4) {
-          const uint32_t w[4] = {raw.a[v4].x, raw.a[v4].y, raw.a[v4].z, raw.a[v4].w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { x[8 * v4 + 2 * e] = bf16lo_to_f32(w[e]); x[8 * v4 + 2 * e + 1] = bf16hi_to_f32(w[e]); }
-        }
-      }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) x[e] = ok ? x[e] * sc : 0.f;
-      store_k_floats(buf, x);
-    }
-  };
-  auto decode_store_v = [&](const VRaw<VB, F32IN>& raw, int tile, int buf) __attribute__((always_inline)) {
-    if (tile < ntc && compressed) {
+      // s * (code - z) evaluated as fma(code, s, -z * s): one conversion and one fused
+      // operation per value (the result differs from Eq. 10's by a rounding of z * s, far
+      // below what the bf16 pair or the f16 value keeps)
       const int ja = tile * kTileK + key_a;
       const bool full = (tile + 1) * kTileK <= t_c;       // uniform; only a cache's last tile can be ragged
-      // rows past the cache's end become zeros (scale zero): their probabilities are zero too
-      const bool ok0 = full || ja < t_c, ok1 = full || ja + 1 < t_c;
-      const float s0 = ok0 ? __uint_as_float(raw.m[0].x) : 0.f, s1 = ok1 ? __uint_as_float(raw.m[1].x) : 0.f;
-      const int z0 = ok0 ? (int32_t)raw.m[0].y : 0, z1 = ok1 ? (int32_t)raw.m[1].y : 0;
-      bool plain = VB != 4;
-      if constexpr (VB == 4) plain = __any((uint32_t)(z0 + kVZLimit) > 2u * kVZLimit || (uint32_t)(z1 + kVZLimit) > 2u * kVZLimit);
-      if (!plain) {
-        if constexpr (VB == 4) {
-          // packed f16: the low half carries row key_a as 1024 + code, the high half row key_a + 1
-          // as 1024 + 16 code (its nibble sits four bits up), with the scale divided by 16
-          const uint32_t sp = pack_f16(s0, s1 * 0.0625f);
-          // (integers: 1024 + z and 1024 + 16 z are exact in f16 for |z| <= kVZLimit)
-          const uint32_t zp = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)(float)(1024 + z0)) |
-                              ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)(float)(1024 + 16 * z1)) << 16);
-          const uint32_t ca = raw.c[0], cb2 = raw.c[1];
-          const uint32_t ev = (ca & 0x0F0F0F0Fu) | ((cb2 & 0x0F0F0F0Fu) << 4);
-          const uint32_t od = ((ca >> 4) & 0x0F0F0F0Fu) | (cb2 & 0xF0F0F0F0u);
+      if constexpr (ROLE_K) {
+        const uint32_t sw[8] = {raw.a[0].x, raw.a[0].y, raw.a[0].z, raw.a[0].w, raw.a[1].x, raw.a[1].y, raw.a[1].z, raw.a[1].w};
+        const uint32_t zw[8] = {raw.a[2].x, raw.a[2].y, raw.a[2].z, raw.a[2].w, raw.a[3].x, raw.a[3].y, raw.a[3].z, raw.a[3].w};
+        float sk[8], nz[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const uint32_t src = (e & 1) ? od : ev;
-            const uint32_t x = __builtin_amdgcn_perm(0u, src, 0x0c000c00u + (uint32_t)(e >> 1) * 0x00010001u);   // byte e / 2 into both halves
-            const uint32_t m = pk_sub((x & 0x00F0000Fu) | kMagic, zp);
-            *reinterpret_cast<uint32_t*>(lds_v[buf] + (co * 8 + e) * kLdsRow + 2 * kp) = pk_mul(m, sp);
-          }
+        for (int e = 0; e < 8; ++e) {
+          sk[e] = __uint_as_float(sw[e]) * sc;
+          nz[e] = -(float)(int32_t)zw[e] * sk[e];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          float f[8], x[8];
+          octet_floats<KB>(raw.c[i], f);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(f[e], sk[e], nz[e]);
+          store_k_split(buf, i, x);        // rows past the cache's end hold finite stale values; their logits are masked
         }
       } else {
-        // plain path: s * (code - z) evaluated as fma(code, s, -z * s), rounded to f16 once
-        const float nz0 = -(float)z0 * s0, nz1 = -(float)z1 * s1;
+        // rows past the cache's end become zeros (scale and offset zero): their probabilities are zero too
+        const bool ok0 = full || ja < t_c, ok1 = full || ja + 1 < t_c;
+        const float s0 = ok0 ? __uint_as_float(raw.m[0].x) : 0.f, s1 = ok1 ? __uint_as_float(raw.m[1].x) : 0.f;
+        const float nz0 = -(float)(int32_t)raw.m[0].y * s0, nz1 = -(float)(int32_t)raw.m[1].y * s1;
         float fa[8], fb[8], va[8], vb[8];
         octet_floats<VB>(raw.c[0], fa);
         octet_floats<VB>(raw.c[1], fb);
@@ -573,54 +412,41 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
           x1[2 * e2] = bf16lo_to_f32(b4[e2]); x1[2 * e2 + 1] = bf16hi_to_f32(b4[e2]);
         }
       }
-      store_v_pair(buf, x0, x1);
+      if constexpr (ROLE_K) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { x0[e] *= sc; x1[e] *= sc; }
+        store_k_split(buf, 0, x0);
+        store_k_split(buf, 1, x1);
+      } else {
+        store_v_pair(buf, x0, x1);
+      }
     }
   };
 
-#ifdef KVX_PROFILE
-  // measurement build: time stamps of two chosen iterations go to the tail of the partials buffer
-  unsigned long long* prof = reinterpret_cast<unsigned long long*>(reinterpret_cast<uint8_t*>(g.part_ml) + (4 << 20)) +
-                             ((int64_t)blockIdx.x * kAttnMaxWaves + wave) * 32;
-  int prof_on = 0, prof_k = 0;
-  auto stamp = [&]() __attribute__((always_inline)) {
-    if (prof_on) {
-      const unsigned long long tt = __builtin_amdgcn_s_memtime();
-      if (lane == 0 && blockIdx.x < 64) prof[prof_k] = tt;
-      ++prof_k;
-    }
-  };
-#define KVX_STAMP() stamp()
-#else
-#define KVX_STAMP()
-#endif
   // ---- one tile: S^T, then softmax and O^T ---------------------------------------------
   const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
   auto compute = [&](int t, int kbuf, int vbuf, bool first) __attribute__((always_inline)) {
     f32x16 s[2][NB];                               // [key half][query block], log2-domain logits minus m
     // The operands come from LDS a few steps ahead of the MFMAs that use them (a step =
     // one key half of one 16-channel slice: the K hi and lo fragments).
-#ifdef KVX_AHEAD
-    constexpr int kAhead = KVX_AHEAD;
-#else
     constexpr int kAhead = 3;
-#endif
-    f16x8 ah[8], al[8], qh[4][NB], ql[4];
+    bf16x8 ah[8], al[8], qh[4][NB], ql[4];
     auto read_k = [&](int i) __attribute__((always_inline)) {
       const int ks = i >> 1, mb = i & 1;
       const int aoff = (mb * 32 + l32) * kLdsRow + ks * 16 + hf * 8;
-      ah[i] = *reinterpret_cast<const f16x8*>(lds_khi[kbuf] + aoff);
-      al[i] = *reinterpret_cast<const f16x8*>(lds_klo[kbuf] + aoff);
+      ah[i] = *reinterpret_cast<const bf16x8*>(lds_khi[kbuf] + aoff);
+      al[i] = *reinterpret_cast<const bf16x8*>(lds_klo[kbuf] + aoff);
     };
     auto read_q = [&](int ks) __attribute__((always_inline)) {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) qh[ks][nb] = __builtin_bit_cast(f16x8, qbase[ks * 64]);
-      if constexpr (F32IN) ql[ks] = __builtin_bit_cast(f16x8, qbase[(1 * 4 + ks) * 64]);
+      for (int nb = 0; nb < NB; ++nb) qh[ks][nb] = __builtin_bit_cast(bf16x8, qbase[ks * 64]);
+      if constexpr (F32IN) ql[ks] = __builtin_bit_cast(bf16x8, qbase[(1 * 4 + ks) * 64]);
     };
     read_q(0);
 #pragma unroll
     for (int i = 0; i < kAhead; ++i) read_k(i);
     read_q(1);
-    KVX_SETPRIO(1);
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int ks = i >> 1, mb = i & 1;
@@ -628,19 +454,16 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
       if (mb == 0 && ks + 2 < 4) read_q(ks + 2);
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        if (ks == 0) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[i], qh[ks][nb], negm[nb], 0, 0, 0);
-        else s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[i], qh[ks][nb], s[mb][nb], 0, 0, 0);
-        s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[i], qh[ks][nb], s[mb][nb], 0, 0, 0);
-        if constexpr (F32IN) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[i], ql[ks], s[mb][nb], 0, 0, 0);
+        if (ks == 0) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], qh[ks][nb], negm[nb], 0, 0, 0);
+        else s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], qh[ks][nb], s[mb][nb], 0, 0, 0);
+        s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], qh[ks][nb], s[mb][nb], 0, 0, 0);
+        if constexpr (F32IN) s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], ql[ks], s[mb][nb], 0, 0, 0);
       }
     }
     // pin the order: the initial reads, then per step the reads issued for later steps and its MFMAs
-#ifndef KVX_NO_PINS
     sched_group<0x100, 2 * kAhead + 2 * NB + (F32IN ? 2 : 0)>();
     pin_qk_steps<NB, F32IN, kAhead>(std::make_integer_sequence<int, 8>{});
-#endif
-    KVX_SETPRIO(0);
-    KVX_STAMP();     // QK issued
+    __builtin_amdgcn_s_setprio(0);
 
     int valid;
     if (t < ntc) valid = min(kTileK, t_c - t * kTileK); else valid = min(kTileK, n - (t - ntc) * kTileK);
@@ -726,8 +549,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) l_run[nb] = l_new[nb];
-    KVX_STAMP();     // softmax done
-    KVX_SETPRIO(1);
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       if (kk + 2 < 4) read_v(kk + 2);
@@ -736,19 +558,14 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) o[cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[kk][cb], pb[nb][kk], o[cb][nb], 0, 0, 0);
     }
-#ifndef KVX_NO_PINS
     sched_group<0x100, 4>();
     sched_group<0x008, 2 * NB>();
     sched_group<0x100, 4>();
     sched_group<0x008, 6 * NB>();
-#endif
-    KVX_SETPRIO(0);
-    KVX_STAMP();     // PV issued
+    __builtin_amdgcn_s_setprio(0);
   };
   auto run_compute = [&](int t, int buf) __attribute__((always_inline)) {
-#ifndef KVX_ABL_NOCOMPUTE
     if (nblk) compute(t, buf, buf, t == tile_begin);
-#endif
   };
 
   // ---- tile loop --------------------------------------------------------------------
@@ -757,79 +574,27 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   // tile's raw data is loaded one interval before it is decoded.
   auto tile_loop = [&](auto rolec) __attribute__((always_inline)) {
     constexpr bool ROLE_K = decltype(rolec)::value;
-    typename std::conditional<ROLE_K, KRaw<KB, F32IN>, VRaw<VB, F32IN>>::type raw;
-#ifdef KVX_ABL_NOWAIT
-    typename std::conditional<ROLE_K, KRaw<KB, F32IN>, VRaw<VB, F32IN>>::type raw2;
-    bool inloop = false;
-    auto load_raw = [&](int tile) __attribute__((always_inline)) {
-      if (inloop) { if constexpr (ROLE_K) load_raw_k(raw2, tile); else load_raw_v(raw2, tile); }
-      else { if constexpr (ROLE_K) load_raw_k(raw, tile); else load_raw_v(raw, tile); }
-    };
-#else
-    auto load_raw = [&](int tile) __attribute__((always_inline)) {
-      if constexpr (ROLE_K) load_raw_k(raw, tile); else load_raw_v(raw, tile);
-    };
-#endif
-    auto decode_store = [&](int tile, int buf, bool first) __attribute__((always_inline)) {
-      if constexpr (ROLE_K) decode_store_k(raw, tile, buf, first); else decode_store_v(raw, tile, buf);
-    };
+    TileRaw<ROLE_K ? KB : VB> raw;
     const int last = tile_end - 1;
-    const bool kc_wave = !ROLE_K && wave == 4;
-#ifdef KVX_ABL_ZERO
-    for (int i = tid; i < 2 * kTileElems; i += blockDim.x) { (&lds_khi[0][0])[i] = 0; (&lds_klo[0][0])[i] = 0; (&lds_v[0][0])[i] = 0; }
-#endif
-    load_raw(tile_begin);
-    if (kc_wave) kc_load(tile_begin + 1);
+    load_raw(rolec, raw, tile_begin);
     stage_q();
-    // the first key tile is decoded from its scales and zero-points directly: its metadata
-    // blocks would cost a second memory round trip before the first barrier
-    decode_store(tile_begin, 0, true);
-    if (kc_wave) {
-      kc_store(tile_begin + 1);
-      kc_load(tile_begin + 2);
-    }
-    load_raw(min(tile_begin + 1, last));
-#ifdef KVX_ABL_NOWAIT
-    inloop = true;
-#endif
+    decode_store(rolec, raw, tile_begin, 0);
+    load_raw(rolec, raw, min(tile_begin + 1, last));
     __syncthreads();
     for (int t = tile_begin; t < tile_end; ++t) {
       const int buf = (t - tile_begin) & 1;
       const bool more = t < last;
-#ifdef KVX_PROFILE
-      prof_on = (t == tile_begin + 10 || t == tile_begin + 11);
-      if (t == tile_begin + 11) prof_k = 8;
-#endif
-      KVX_STAMP();       // 0: iteration start
       if constexpr (ROLE_K) {
-        run_compute(t, buf);      // 1, 2, 3
-#ifndef KVX_ABL_NODECODE
-        if (more) decode_store(t + 1, buf ^ 1, false);
-#endif
-        KVX_STAMP();     // 4: decoded
-#ifndef KVX_ABL_NOLOAD
-        load_raw(min(t + 2, last));
-#endif
-        KVX_STAMP();     // 5: loads issued
+        run_compute(t, buf);
+        if (more) decode_store(rolec, raw, t + 1, buf ^ 1);
+        load_raw(rolec, raw, min(t + 2, last));
       } else {
-        if (kc_wave) kc_store(t + 2);       // the blocks of tile t + 2, loaded one interval ago
-#ifndef KVX_ABL_NODECODE
-        if (more) decode_store(t + 1, buf ^ 1, false);
-#endif
-        KVX_STAMP();     // 1: decoded
-#ifndef KVX_ABL_NOLOAD
-        load_raw(min(t + 2, last));
-        if (kc_wave) kc_load(t + 3);
-#endif
-        KVX_STAMP();     // 2: loads issued
-        run_compute(t, buf);      // 3, 4, 5
+        if (more) decode_store(rolec, raw, t + 1, buf ^ 1);
+        load_raw(rolec, raw, min(t + 2, last));
+        run_compute(t, buf);
       }
       __syncthreads();
-      KVX_STAMP();       // 6: past the barrier
     }
-#ifdef KVX_ABL_NOWAIT
-    if (raw2.c == raw.c && tile_end == 12345) lds_kc[0][lane] = make_uint4(1, 2, 3, 4);
-#endif
   };
   if (tile_begin < tile_end) {
     if (wave < 4) {
@@ -840,14 +605,8 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
       stage_q();
       __syncthreads();
       for (int t = tile_begin; t < tile_end; ++t) {
-#ifdef KVX_PROFILE
-        prof_on = (t == tile_begin + 10 || t == tile_begin + 11);
-        if (t == tile_begin + 11) prof_k = 8;
-#endif
-        KVX_STAMP();     // 0
-        run_compute(t, (t - tile_begin) & 1);   // 1, 2, 3
+        run_compute(t, (t - tile_begin) & 1);
         __syncthreads();
-        KVX_STAMP();     // 4: past the barrier
       }
     }
   }

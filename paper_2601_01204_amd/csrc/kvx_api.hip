@@ -106,14 +106,28 @@ int validate(const kv_config* c) {
   return KV_OK;
 }
 
+// Key-range splits per (item, head, query tile) column.  A workgroup occupies a compute
+// unit by itself, so a launch runs in rounds of `target_wgs` workgroups; the estimate below
+// is rounds x (tiles per workgroup + a fixed per-workgroup cost of about three tiles for the
+// first loads and the partial-result store), and the split count with the smallest
+// estimate wins (fewer splits on ties: less merge traffic).
 int pick_splits(const kv_handle* h, int n_items, int min_tiles) {
   const Geometry& g = h->geo;
   int s;
   if (h->splits_override > 0) {
     s = h->splits_override;
   } else {
-    const int base = n_items * g.H * g.n_qtiles;
-    s = (h->target_wgs + base / 2) / base;
+    const int64_t base = (int64_t)n_items * g.H * g.n_qtiles;
+    const int tiles = std::max(1, std::min(min_tiles, 1 << 20));
+    // up to two rounds' worth of workgroups, and at least four splits to choose from
+    const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, (2 * (int64_t)h->target_wgs) / base));
+    double best = 0.0;
+    s = 1;
+    for (int c = 1; c <= cap; ++c) {
+      const int64_t rounds = (base * c + h->target_wgs - 1) / h->target_wgs;
+      const double cost = (double)rounds * ((double)tiles / c + 3.0) + (c > 1 ? 1.0 : 0.0);
+      if (c == 1 || cost < best * 0.98) { best = cost; s = c; }
+    }
   }
   s = std::max(1, std::min(s, (int)kMaxSplits));
   s = std::min(s, std::max(1, min_tiles));
@@ -189,7 +203,6 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   L.k_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * k_row, 256);
   L.k_scale = off; off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
   L.k_zero = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
-  L.k_att = off;   off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kAttBlock), 256);
   L.v_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * v_row, 256);
   L.v_meta = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * (int64_t)sizeof(VMeta)), 256);
   L.ids = off;     off = align_up(off + (int64_t)g.t_cap * 4, 256);
@@ -210,7 +223,12 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   const int64_t n_caches = (int64_t)c.n_streams * c.n_layers;
   h->caches.assign((size_t)n_caches, CacheState());
   h->slots_cap = 0;
-  for (int items = 1; items <= kMaxItems; ++items) h->slots_cap = std::max(h->slots_cap, items * std::max(pick_splits(h, items, 1 << 30), 1));
+  for (int items = 1; items <= kMaxItems; ++items) {
+    // the most splits pick_splits can choose for this many items with 256 target workgroups
+    const int64_t base = (int64_t)items * g.H * g.n_qtiles;
+    const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, 512 / base));
+    h->slots_cap = std::max(h->slots_cap, items * cap);
+  }
   h->slots_cap = std::max(h->slots_cap, (int32_t)kMaxSplits);
   h->bytes_arena = n_caches * L.cache_bytes;
   h->bytes_scratch = n_caches * S.bytes;
@@ -395,7 +413,7 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
   memset(s, 0, sizeof *s);
   s->bytes_allocated = h->bytes_arena + h->bytes_scratch + h->bytes_part;
   s->bytes_k_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.k_bits / 8);
-  s->bytes_k_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.g_cap * (kHeadDim * 8 + kAttBlock));
+  s->bytes_k_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.g_cap * (kHeadDim * 8));
   s->bytes_v_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.v_bits / 8);
   s->bytes_v_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * 8);
   s->bytes_ids = nc * halves * (int64_t)g.t_cap * 4;
@@ -422,7 +440,7 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
     s->bytes_live_per_cache = 2 * (int64_t)g.H * T * kHeadDim * 2;
   } else {
     const int64_t groups = (T + g.k_group - 1) / g.k_group;
-    s->bytes_live_per_cache = (int64_t)g.H * T * kHeadDim * g.k_bits / 8 + (int64_t)g.H * groups * (kHeadDim * 8 + kAttBlock) +
+    s->bytes_live_per_cache = (int64_t)g.H * T * kHeadDim * g.k_bits / 8 + (int64_t)g.H * groups * (kHeadDim * 8) +
                               (int64_t)g.H * T * kHeadDim * g.v_bits / 8 + (int64_t)g.H * T * (kHeadDim / g.v_group) * 8 + T * 4;
   }
   return KV_OK;
@@ -539,13 +557,6 @@ int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches) {
   h->timed.clear();
   return KV_OK;
 }
-
-#ifdef KVX_PROFILE
-int kv_debug_read(kv_handle* h, void* dst, int64_t offset, int64_t bytes) {
-  hipDeviceSynchronize();
-  return hipMemcpy(dst, reinterpret_cast<uint8_t*>(h->part_ml) + offset, (size_t)bytes, hipMemcpyDeviceToHost) == hipSuccess ? 0 : -5;
-}
-#endif
 
 int kv_set_option(kv_handle* h, const char* name, int64_t value) {
   if (!h) return KV_E_INVAL;

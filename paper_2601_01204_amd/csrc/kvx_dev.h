@@ -23,7 +23,6 @@ struct CacheLayout {
   int64_t k_codes;    // [H][t_cap][d * k_bits / 8]
   int64_t k_scale;    // [H][g_cap][d] float
   int64_t k_zero;     // [H][g_cap][d] int32
-  int64_t k_att;      // [H][g_cap][kAttBlock bytes]: the key metadata in the form the attention kernel consumes (see below)
   int64_t v_codes;    // [H][t_cap][d * v_bits / 8]
   int64_t v_meta;     // [H][t_cap][d / v_group] VMeta
   int64_t ids;        // [t_cap] int32
@@ -93,35 +92,6 @@ struct KvxBatch {
   int32_t pad;
   Item items[kMaxItems];
 };
-
-// ---- key metadata for attention ---------------------------------------------------
-// A cached key is s * (code - z) (Sec. 3.3 Eq. 10).  With m = code - z a small integer and
-// sk = s * (softmax scale * log2 e) split as sk = a + b, a = the top kAttSplitBits
-// significant bits of sk, the product m * a is exact in f16 and m * b is a small correction,
-// so the attention kernel forms the key as an f16 pair (m * a, m * b) with packed f16
-// arithmetic.  Per (head, group) a block of kAttBlock bytes holds three planes of 64 f16
-// (a, b and 1024 + z per channel) and a 16-byte tail whose first word is nonzero if some
-// channel of the group cannot take that path (zero-point out of range, scale outside f16's
-// normal range).  The channels of a plane are stored in the order the attention kernel
-// keeps them in LDS: codes that sit 16 bits apart in a code word become the two halves of
-// one packed value.
-constexpr int kAttBlock = 3 * kHeadDim * 2 + 16;
-constexpr int kAttSplitBits = 6;          // significant bits of a: |m| < 32 keeps m * a within f16's 11
-constexpr int kAttZMin = -16, kAttZMax = 31;
-// position (0..15) of channel i (0..15) of a 16-channel slice in the stored order
-template <int B>
-__host__ __device__ constexpr int k_att_pos(int i) {
-  if (B == 4) return (i & 8) | (((i & 3) << 1) | ((i >> 2) & 1));     // per octet: 0,4,1,5,2,6,3,7
-  if (B == 2) return ((i & 7) << 1) | (i >> 3);                       // per slice: 0,8,1,9,...,7,15
-  return i;
-}
-// channel (0..15) held at stored position p (0..15)
-template <int B>
-__host__ __device__ constexpr int k_att_chan(int p) {
-  if (B == 4) return (p & 8) | ((p & 7) >> 1) | ((p & 1) << 2);
-  if (B == 2) return (p >> 1) | ((p & 1) << 3);
-  return p;
-}
 
 // ---- device-side address helpers ------------------------------------------------
 __device__ __forceinline__ uint8_t* cache_half(const Geometry& g, int cache, int half) {

@@ -258,19 +258,6 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
       if (!dv.safe) unsafe_scales = 1;
       reinterpret_cast<float*>(nxt + g.lay.k_scale)[moff] = s;
       reinterpret_cast<int32_t*>(nxt + g.lay.k_zero)[moff] = z;
-      // the same metadata in the form the attention kernel consumes (a function of s and z
-      // alone, so carried groups get the values they had)
-      const float sk = s * g.scale_log2;
-      const float sk_a = __uint_as_float(__float_as_uint(sk) & (0xFFFFFFFFu << (24 - kAttSplitBits)));
-      const float sk_b = sk - sk_a;
-      const bool plain = B == 8 || z < kAttZMin || z > kAttZMax || !(fabsf(sk_a) >= 0x1p-14f) || !(fabsf(sk_a) < 1024.f);
-      uint8_t* blk = nxt + g.lay.k_att + ((int64_t)h * g.g_cap + ggrp) * kAttBlock;
-      uint16_t* att = reinterpret_cast<uint16_t*>(blk) + (c & ~15) + k_att_pos<B>(c & 15);
-      att[0] = __builtin_bit_cast(uint16_t, (_Float16)sk_a);
-      att[kHeadDim] = __builtin_bit_cast(uint16_t, (_Float16)sk_b);
-      att[2 * kHeadDim] = __builtin_bit_cast(uint16_t, (_Float16)(plain ? 1024.f : 1024.f + (float)z));
-      const bool any_plain = __any(plain);            // the 64 threads of a group are one wave
-      if (c < 4) reinterpret_cast<uint32_t*>(blk + 3 * kHeadDim * 2)[c] = any_plain ? 1u : 0u;
     }
   }
   __syncthreads();

@@ -6,12 +6,17 @@
 // of additions stated at the kernel (compiled without FMA contraction).
 #include "kvx_dev.h"
 
+#include <algorithm>
+
 namespace kvx {
 
-// Eq. 2-3: one block per pooled row, one thread per (head, channel).  Per (head, channel):
-// add the row's tokens in ascending order starting from the first, divide by the group
-// size; then per channel add heads 0..H-1 in order starting from zero, divide by H.
-__global__ __launch_bounds__(1024) void pool_rows_kernel(const KvxBatch b) {
+// Eq. 2-3: one block per pooled row, eight lanes per head, eight channels per lane.  Per
+// (head, channel): add the row's tokens in ascending order starting from the first, divide
+// by the group size; then per channel add heads 0..H-1 in order starting from zero, divide
+// by H.  A group's tokens are requested sixteen at a time before any is added, so a row
+// costs one memory round trip.
+constexpr int kPoolBatch = 16;
+__global__ __launch_bounds__(512) void pool_rows_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.y];
   if (!it.prune) return;
@@ -24,46 +29,82 @@ __global__ __launch_bounds__(1024) void pool_rows_kernel(const KvxBatch b) {
     a = g.n_special + (row - g.n_special) * g.pool_group;
     e = min(a + g.pool_group, g.n);
   }
-  __shared__ float pooled[64][kHeadDim];     // up to 64 heads
-  const int c = threadIdx.x & 63;
-  for (int h = threadIdx.x >> 6; h < g.H; h += 16) {
-    float acc;
-    if (g.in_f32) {
-      const float* q = reinterpret_cast<const float*>(it.q);
-      acc = q[(int64_t)a * g.tok_stride + (int64_t)h * g.head_stride + c];
-#pragma unroll 8
-      for (int t = a + 1; t < e; ++t) acc = acc + q[(int64_t)t * g.tok_stride + (int64_t)h * g.head_stride + c];
-    } else {
-      const uint16_t* q = reinterpret_cast<const uint16_t*>(it.q);
-      acc = __uint_as_float((uint32_t)q[(int64_t)a * g.tok_stride + (int64_t)h * g.head_stride + c] << 16);
-#pragma unroll 8
-      for (int t = a + 1; t < e; ++t)
-        acc = acc + __uint_as_float((uint32_t)q[(int64_t)t * g.tok_stride + (int64_t)h * g.head_stride + c] << 16);
+  __shared__ __attribute__((aligned(16))) float pooled[64][kHeadDim];     // up to 64 heads
+  const int h = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 8;
+  if (h < g.H) {
+    float acc[8];
+    for (int t0 = a; t0 < e; t0 += kPoolBatch) {
+      float v[kPoolBatch][8];
+#pragma unroll
+      for (int k = 0; k < kPoolBatch; ++k) {
+        const int t = min(t0 + k, e - 1);                  // clamped: a repeated token is loaded but not added
+        const int64_t off = (int64_t)t * g.tok_stride + (int64_t)h * g.head_stride + c0;
+        if (g.in_f32) {
+          const float4* q = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(it.q) + off);
+          const float4 x0 = q[0], x1 = q[1];
+          v[k][0] = x0.x; v[k][1] = x0.y; v[k][2] = x0.z; v[k][3] = x0.w;
+          v[k][4] = x1.x; v[k][5] = x1.y; v[k][6] = x1.z; v[k][7] = x1.w;
+        } else {
+          const uint4 x = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(it.q) + off);
+          const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            v[k][2 * j] = __uint_as_float(w[j] << 16);
+            v[k][2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+          }
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < kPoolBatch; ++k) {
+        if (t0 + k < e) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[j] = (t0 + k == a) ? v[k][j] : acc[j] + v[k][j];
+        }
+      }
     }
-    pooled[h][c] = acc / (float)(e - a);
+    const float cnt = (float)(e - a);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) pooled[h][c0 + j] = acc[j] / cnt;
   }
   __syncthreads();
   if (threadIdx.x < 64) {
+    const int c = threadIdx.x;
     float acc = 0.f;
-    for (int h = 0; h < g.H; ++h) acc = acc + pooled[h][c];
+    for (int hh = 0; hh < g.H; ++hh) acc = acc + pooled[hh][c];
     reinterpret_cast<float*>(cache_scratch(g, it.cache) + g.sl.qbar)[row * kHeadDim + c] = acc / (float)g.H;
   }
 }
 
 // The row mean of Eq. 6 pulled inside the product: q~ = (pooled rows added in ascending
-// order from zero) / N_pooled, one thread per channel.  A kernel of its own, so that the
-// pooled rows reach it through the kernel boundary and no block has to fence.
-__global__ __launch_bounds__(64) void pool_mean_kernel(const KvxBatch b) {
+// order from zero) / N_pooled.  A kernel of its own, so that the pooled rows reach it
+// through the kernel boundary and no block has to fence.  The rows are brought into LDS
+// 128 at a time by the whole block (one memory round trip per 128 rows), then one thread
+// per channel adds them in order.
+constexpr int kMeanRows = 128;
+__global__ __launch_bounds__(1024) void pool_mean_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.x];
   if (!it.prune) return;
   uint8_t* sc = cache_scratch(g, it.cache);
-  const float* qbar = reinterpret_cast<const float*>(sc + g.sl.qbar);
-  const int c = threadIdx.x;
+  const float4* qbar = reinterpret_cast<const float4*>(sc + g.sl.qbar);
+  __shared__ __attribute__((aligned(16))) float rows[kMeanRows][kHeadDim];
+  const int tid = threadIdx.x;
   float acc = 0.f;
-#pragma unroll 16
-  for (int i = 0; i < g.n_pooled; ++i) acc = acc + qbar[i * kHeadDim + c];
-  reinterpret_cast<float*>(sc + g.sl.qt)[c] = acc / (float)g.n_pooled;
+  for (int r0 = 0; r0 < g.n_pooled; r0 += kMeanRows) {
+    const int cnt = min(kMeanRows, g.n_pooled - r0);
+    // 16 float4 per row: threads 0..1023 cover 64 rows per step
+#pragma unroll
+    for (int k = 0; k < kMeanRows / 64; ++k) {
+      const int r = k * 64 + (tid >> 4);
+      if (r < cnt) *reinterpret_cast<float4*>(&rows[r][(tid & 15) * 4]) = qbar[(int64_t)(r0 + r) * 16 + (tid & 15)];
+    }
+    __syncthreads();
+    if (tid < kHeadDim) {
+      for (int r = 0; r < cnt; ++r) acc = acc + rows[r][tid];
+    }
+    __syncthreads();
+  }
+  if (tid < kHeadDim) reinterpret_cast<float*>(sc + g.sl.qt)[tid] = acc / (float)g.n_pooled;
 }
 
 template <int B>
@@ -128,8 +169,8 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
 }
 
 void launch_pool(const KvxBatch& b, hipStream_t st) {
-  hipLaunchKernelGGL(pool_rows_kernel, dim3(b.g.n_pooled, b.n_items), dim3(1024), 0, st, b);
-  hipLaunchKernelGGL(pool_mean_kernel, dim3(b.n_items), dim3(64), 0, st, b);
+  hipLaunchKernelGGL(pool_rows_kernel, dim3(b.g.n_pooled, b.n_items), dim3(std::max(64, 8 * b.g.H)), 0, st, b);
+  hipLaunchKernelGGL(pool_mean_kernel, dim3(b.n_items), dim3(1024), 0, st, b);
 }
 
 void launch_score(const KvxBatch& b, int max_tc, hipStream_t st) {

@@ -6,9 +6,12 @@
 //
 // One workgroup of 1024 threads per cache.  Each thread keeps its share of the keys in
 // registers (element i of thread t is position t + 1024 i, so the loads coalesce); a
-// 4-pass most-significant-byte-first radix select over LDS histograms finds the key of
-// the last token to drop; keep flags go to LDS and a block scan over contiguous chunks
-// compacts the survivors in position order.
+// 3-pass most-significant-digit-first radix select (12, 10 and 10 bits) over an LDS
+// histogram finds the key of the last token to drop; keep flags go to LDS and a block scan
+// over contiguous chunks compacts the survivors in position order.  The first digit takes
+// sign, exponent and three mantissa bits, so scores of one magnitude still spread over
+// several bins and the LDS atomics of a wave rarely pile onto one address; after it only
+// the keys of one bin remain candidates.
 #include "kvx_dev.h"
 
 namespace kvx {
@@ -73,6 +76,8 @@ __global__ __launch_bounds__(256) void score_sum_kernel(const KvxBatch b) {
   reinterpret_cast<uint32_t*>(sc + g.sl.keys)[i] = order_key(s);
 }
 
+constexpr int kSelBins = 4096;
+
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.x];
@@ -87,8 +92,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   int32_t* keep = reinterpret_cast<int32_t*>(sc + g.sl.keep);
   int32_t* sel = reinterpret_cast<int32_t*>(sc + g.sl.sel);
   const int tid = threadIdx.x;
+  const int used = (M + kSelThreads - 1) / kSelThreads;      // keys per thread actually present (<= kSelPerThread)
 
-  __shared__ int hist[256];
+  __shared__ int hist[kSelBins];
   __shared__ int wave_sums[16];
   __shared__ uint32_t sh_prefix;
   __shared__ int sh_remaining;
@@ -100,7 +106,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
 #pragma unroll
   for (int k = 0; k < kSelPerThread; ++k) {
     const int i = tid + k * kSelThreads;
-    key[k] = i < M ? keys[i] : 0u;
+    key[k] = (k < used && i < M) ? keys[i] : 0u;
   }
   if (tid == 0) {
     sh_prefix = 0u;
@@ -109,33 +115,53 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   }
   __syncthreads();
 
-  // Key of the n_drop-th smallest element.
+  // Key of the n_drop-th smallest element, digit by digit.
   uint32_t mask = 0u;
-  for (int pass = 3; pass >= 0; --pass) {
-    const int shift = 8 * pass;
-    if (tid < 256) hist[tid] = 0;
+#pragma unroll
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+    const int bins = pass == 0 ? 4096 : 1024;
+    for (int i = tid; i < bins; i += kSelThreads) hist[i] = 0;
     __syncthreads();
     const uint32_t prefix = sh_prefix;
 #pragma unroll
     for (int k = 0; k < kSelPerThread; ++k) {
-      const int i = tid + k * kSelThreads;
-      if (i < M && (key[k] & mask) == prefix) atomicAdd(&hist[(key[k] >> shift) & 255u], 1);
+      if (k < used) {
+        const int i = tid + k * kSelThreads;
+        if (i < M && (key[k] & mask) == prefix) atomicAdd(&hist[(key[k] >> shift) & (uint32_t)(bins - 1)], 1);
+      }
     }
     __syncthreads();
     {
-      // the bin holding the rem-th smallest candidate: counts before each bin by a block scan
-      const int cnt = tid < 256 ? hist[tid] : 0;
+      // the bin holding the rem-th smallest candidate: each thread owns bins / 1024 consecutive
+      // bins, counts before each thread's bins by a block scan
+      const int per = bins / kSelThreads;                   // 4 or 1
+      int c4[4] = {0, 0, 0, 0};
+      int cnt = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (j < per) { c4[j] = hist[tid * per + j]; cnt += c4[j]; }
       int tot_unused;
-      const int before = block_scan_excl(cnt, wave_sums, tot_unused);
+      int before = block_scan_excl(cnt, wave_sums, tot_unused);
       const int rem = sh_remaining;
       __syncthreads();
-      if (tid < 256 && before < rem && before + cnt >= rem) {
-        sh_remaining = rem - before;
-        sh_prefix = prefix | ((uint32_t)tid << shift);
-        sh_eq = cnt;                                 // after the last pass: keys equal to the threshold
+      if (before < rem && before + cnt >= rem) {           // exactly one thread
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (j < per) {
+            if (before < rem && before + c4[j] >= rem) {
+              sh_remaining = rem - before;
+              sh_prefix = prefix | ((uint32_t)(tid * per + j) << shift);
+              sh_eq = c4[j];                                // after the last pass: keys equal to the threshold
+              before = rem;                                 // no later bin matches
+            } else {
+              before += c4[j];
+            }
+          }
+        }
       }
     }
-    mask |= 0xFFu << shift;
+    mask |= (uint32_t)(bins - 1) << shift;
     __syncthreads();
   }
   const uint32_t thr = sh_prefix;
@@ -147,7 +173,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
 #pragma unroll
   for (int k = 0; k < kSelPerThread; ++k) {
     const int i = tid + k * kSelThreads;
-    if (i < M) flags[i] = key[k] > thr ? 1 : (key[k] == thr ? (eq_keep == 0 ? 0 : 2) : 0);
+    if (k < used && i < M) flags[i] = key[k] > thr ? 1 : (key[k] == thr ? (eq_keep == 0 ? 0 : 2) : 0);
   }
   __syncthreads();
 
