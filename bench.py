@@ -24,7 +24,7 @@ PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
 # profiles/attn_kernel_vggt_layer_counters.txt), fetch counter scaled by 2.00, write by 1.00.
-ATTENTION_TRAFFIC_BYTES = 38.65e6
+ATTENTION_TRAFFIC_BYTES = 34.25e6
 
 
 def oracle_baseline(w, frames_total=18, steady_from=9):

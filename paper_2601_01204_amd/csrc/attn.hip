@@ -35,6 +35,8 @@
 // vector stretches fall at different times between two barriers.
 #include "kvx_dev.h"
 
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 #include <utility>
 
@@ -698,17 +700,23 @@ __global__ __launch_bounds__(256) void combine_kernel(const KvxBatch b) {
 }
 
 template <int KB, int VB>
-static void launch_attn_t(const KvxBatch& b, hipStream_t st) {
+static void launch_attn_t(const KvxBatch& b, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const Geometry& g = b.g;
   dim3 grid(g.n_qtiles * g.H * b.n_items * g.n_splits);
   const dim3 block(64 * (g.q_blocks > 8 ? g.q_blocks : 8));      // a wave per query block, at least the 8 staging waves
-  if (g.in_f32) hipLaunchKernelGGL((attn_kernel<KB, VB, true>), grid, block, 0, st, b);
-  else hipLaunchKernelGGL((attn_kernel<KB, VB, false>), grid, block, 0, st, b);
+  // with events: the runtime stamps them at the kernel's own start and end (what a kernel trace reports)
+  if (ev_start) {
+    if (g.in_f32) hipExtLaunchKernelGGL((attn_kernel<KB, VB, true>), grid, block, 0, st, ev_start, ev_stop, 0, b);
+    else hipExtLaunchKernelGGL((attn_kernel<KB, VB, false>), grid, block, 0, st, ev_start, ev_stop, 0, b);
+  } else {
+    if (g.in_f32) hipLaunchKernelGGL((attn_kernel<KB, VB, true>), grid, block, 0, st, b);
+    else hipLaunchKernelGGL((attn_kernel<KB, VB, false>), grid, block, 0, st, b);
+  }
 }
 
-void launch_attention(const KvxBatch& b, int /*max_tiles*/, hipStream_t st) {
+void launch_attention(const KvxBatch& b, int /*max_tiles*/, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int kb = b.g.uncompressed ? 4 : b.g.k_bits, vb = b.g.uncompressed ? 4 : b.g.v_bits;
-#define KVX_CASE(K, V) if (kb == K && vb == V) { launch_attn_t<K, V>(b, st); return; }
+#define KVX_CASE(K, V) if (kb == K && vb == V) { launch_attn_t<K, V>(b, st, ev_start, ev_stop); return; }
   KVX_CASE(4, 4) KVX_CASE(8, 8) KVX_CASE(2, 4) KVX_CASE(2, 2) KVX_CASE(4, 8) KVX_CASE(8, 4) KVX_CASE(4, 2) KVX_CASE(2, 8) KVX_CASE(8, 2)
 #undef KVX_CASE
 }

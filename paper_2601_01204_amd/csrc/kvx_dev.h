@@ -102,7 +102,7 @@ __device__ __forceinline__ uint8_t* cache_scratch(const Geometry& g, int cache) 
 }
 
 // ---- launchers (each enqueues on `st`, never synchronises) ----------------------
-void launch_attention(const KvxBatch& b, int max_tiles, hipStream_t st);
+void launch_attention(const KvxBatch& b, int max_tiles, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void launch_combine(const KvxBatch& b, hipStream_t st);
 void launch_pool(const KvxBatch& b, hipStream_t st);
 void launch_score(const KvxBatch& b, int max_tc, hipStream_t st);
