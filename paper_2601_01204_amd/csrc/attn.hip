@@ -26,12 +26,14 @@
 // wave-uniform branch) is m raised for every row whose largest key exceeds it by more
 // than kRescaleGap, O and l are rescaled and the tile's probabilities are formed again.
 //
-// Schedule.  Measured on gfx950, an MFMA overlaps only one or two vector instructions of
-// its own wave and about a quarter of its cycles with vector work of other waves, so a
-// SIMD is close to a serial resource and what matters is that it always has a wave that
-// can issue.  A SIMD holds up to three waves of the workgroup (w, w + 4, w + 8), each
-// with the same matrix work; waves 0-3 compute a tile and then stage K of the next one,
-// waves 4-7 stage V first and then compute, waves 8-11 only compute, so their MFMA and
+// Schedule.  A wave issues in order.  Measured on gfx950, its independent vector
+// instructions do run under its own MFMAs, but every 16-byte LDS operand read holds the
+// wave for about as long as it holds the SIMD's LDS return path (16 cycles), so a single
+// wave that interleaves its reads, MFMAs and softmax arithmetic gains little over doing
+// them one after the other; the overlap has to come from different waves of a SIMD being
+// in different phases.  A SIMD holds up to three waves of the workgroup (w, w + 4, w + 8),
+// each with the same matrix work; waves 0-3 compute a tile and then stage K of the next
+// one, waves 4-7 stage V first and then compute, waves 8-11 only compute, so their MFMA and
 // vector stretches fall at different times between two barriers.
 #include "kvx_dev.h"
 

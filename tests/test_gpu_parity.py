@@ -106,3 +106,50 @@ def test_vggt_hires_int2_keys_across_onset():
     of one stream and layer (pruning starts at the 18th)."""
     w = si.WORKLOADS["vggt_hires"]
     pu.run_stream(w, 20, check_every=6)
+
+
+def _run_custom_stream(w, frames_qkv):
+    """Free-running parity on explicitly given frames."""
+    import torch
+    from oracle import xstream_oracle as xo
+    h = pu.make_handle(w)
+    cache = xo.OracleCache(pu.oracle_cfg(w))
+    for t, (q, k, v) in enumerate(frames_qkv):
+        ref = cache.step(q, k, v)
+        tq, tk, tv = (pu.to_device(a, w) for a in (q, k, v))
+        out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+        h.step(tq, tk, tv, out)
+        torch.cuda.synchronize()
+        pu.check_output(out.float().cpu().numpy(), ref, f"{w.name} frame {t}")
+        pu.check_state(h.export(), cache, f"{w.name} frame {t}")
+    h.close()
+
+
+def test_selection_with_tied_scores():
+    """The same frame fed again and again: every middle token has duplicates with bit-identical
+    scores, so the cut of the top-k falls inside runs of equal keys and the lower positions
+    must win; the duplicated keys also give key groups whose codes repeat."""
+    w = si.Workload("ties", 2, 64, 90, 5, 16, 400, 9, 1, 1, 4, 64, 4, 64, "bf16", 21)
+    sigma = si.key_channel_scales(w)
+    base = [si.frame_qkv(w, t, sigma=sigma) for t in range(2)]
+    _run_custom_stream(w, [base[t % 2] for t in range(9)])
+
+
+def test_zero_keys_give_signed_zero_scores_and_constant_groups():
+    """Keys that are zero in whole frames and constant in others: scores of +0.0 / -0.0 (ordered
+    -0 < +0 by the key image), groups with max == min (scale |min| or 1, code 0), and a cut
+    through a run of equal scores."""
+    w = si.Workload("zeros", 2, 64, 70, 5, 16, 300, 8, 1, 1, 4, 64, 4, 64, "f32", 22)
+    sigma = si.key_channel_scales(w)
+    frames = []
+    for t in range(8):
+        q, k, v = si.frame_qkv(w, t, sigma=sigma)
+        if t in (1, 2):
+            k = np.zeros_like(k)
+        elif t == 3:
+            k = np.full_like(k, -0.75)
+        elif t == 4:
+            k = np.zeros_like(k)
+            k[:, :, ::2] = 0.5
+        frames.append((q, k, v))
+    _run_custom_stream(w, frames)
