@@ -56,11 +56,15 @@ def oracle_baseline(w, frames_total=18, steady_from=9):
 
 
 def aux_measurements(torch, kvx, si, dev, frames, peak_hbm):
-    """Two side measurements, outside the timed region of the headline number:
+    """Side measurements, outside the timed region of the headline number:
     (1) the attention kernel alone on the benchmark workload (no second stream, all CUs);
     (2) one batched step over the 24 independent layer caches of the 'vggt_stack' workload
         (budget 16384), which gives the bandwidth kernels launches large enough to be judged
-        against HBM peak."""
+        against HBM peak;
+    (3) the uncompressed bf16 cache (plain Eq. 1 over every past frame) at 100, 250 and 500 frames
+        of the benchmark workload: per-frame time and cache bytes grow with the stream, which is
+        the growth the compressed cache's flat cost is set against (Sec. 4.3);
+    (4) the matrix-instruction rate and the copy bandwidth this machine sustains."""
     out = {}
     w = si.WORKLOADS["vggt_layer"]
     n, H, d, L = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens
@@ -126,6 +130,34 @@ def aux_measurements(torch, kvx, si, dev, frames, peak_hbm):
         "kv_bytes_live_per_layer": h.stats()["bytes_live_per_cache"],
     }
     h.close()
+
+    w = si.WORKLOADS["vggt_layer"]
+    n, H, d = w.tokens_per_frame, w.n_heads, w.head_dim
+    marks = (100, 250, 500)
+    h = kvx.KvHandle(n_heads=H, tokens_per_frame=n, n_special=w.n_special, pool_group=w.pool_group,
+                     budget_tokens=w.budget_tokens, mode=kvx.KV_UNCOMPRESSED_BF16, max_frames=marks[-1])
+    o = torch.empty((n, H, d), dtype=torch.bfloat16, device=dev)
+    growth = {}
+    t = 0
+    for m in marks:
+        while t < m - 5:
+            h.step(*frames[t % len(frames)], o)
+            t += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while t < m:
+            h.step(*frames[t % len(frames)], o)
+            t += 1
+        torch.cuda.synchronize()
+        growth[str(m)] = {"ms_per_frame": round((time.perf_counter() - t0) * 1e3 / 5, 3),
+                          "cache_bytes": 2 * H * m * n * d * 2}
+    out["uncompressed_bf16_by_frames"] = growth
+    h.close()
+
+    # what this machine sustains: a register-resident bf16 MFMA loop on every CU (~5 ms per launch,
+    # long enough for the clock to settle under the power limit) and a 1 GiB streaming copy
+    out["machine"] = {"mfma_bf16_sustained_TFLOP/s": round(kvx.probe_mfma_bf16(50000, 3), 1),
+                      "hbm_copy_GB/s": round(kvx.probe_copy(1 << 30, 3), 1)}
     return out
 
 
@@ -139,7 +171,7 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="run the cache update after attention instead of beside it")
     ap.add_argument("--no-aux", action="store_true", help="skip the auxiliary measurements (standalone attention, 24-layer batched step)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run three 1 GiB device-to-device copies, a known-size reference for HBM byte counters")
+                    help="also run 1 GiB device-to-device copies (copy_probe_kernel), the known-size reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -163,12 +195,7 @@ def main():
         h.set_option("overlap_update", 0)
 
     if args.copy_calibration:
-        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        c = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
-        for _ in range(3):
-            a.copy_(c)
-        torch.cuda.synchronize()
-        del a, c
+        kvx.probe_copy(1 << 30, 3)
 
     # a ring of distinct frames, resident in HBM
     ring = w.frames

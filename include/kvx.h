@@ -183,6 +183,19 @@ int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches);
  *                                 order on hip_stream */
 int kv_set_option(kv_handle* h, const char* name, int64_t value);
 
+/* Machine probes (measurement aids, no handle needed; they allocate and free their own
+ * device buffers and wait for their launches before returning).
+ *   kv_probe_mfma_bf16: `repeats` launches of a register-resident loop of `iters` x 4 bf16
+ *     32x32x16 matrix instructions per wave, eight waves on every compute unit, after one warm-up
+ *     launch; writes the mean rate in TFLOP/s to *tflops (host).  This is the matrix-core rate the machine sustains under
+ *     its power limit, the ceiling beside the published peak that Eq. 1's kernel is quoted against.
+ *   kv_probe_copy: `repeats` streaming device-to-device copies of `bytes` bytes (multiple of 16,
+ *     4 KiB .. 16 GiB) after one warm-up copy; writes the mean rate in GB/s (bytes read + bytes written) to
+ *     *gbytes_per_s (host).  Also the known-size launch that HBM byte counters are scaled by.
+ * Both return KV_OK or a negative kv_status. */
+int kv_probe_mfma_bf16(int32_t iters, int32_t repeats, void* hip_stream, double* tflops);
+int kv_probe_copy(int64_t bytes, int32_t repeats, void* hip_stream, double* gbytes_per_s);
+
 #ifdef __cplusplus
 }
 #endif

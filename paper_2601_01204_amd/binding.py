@@ -77,11 +77,31 @@ def load_library():
     lib.kv_set_timing.argtypes = [P, C.c_uint32]
     lib.kv_read_timing.argtypes = [P, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.kv_set_option.argtypes = [P, C.c_char_p, C.c_int64]
+    lib.kv_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, P, C.POINTER(C.c_double)]
+    lib.kv_probe_copy.argtypes = [C.c_int64, C.c_int32, P, C.POINTER(C.c_double)]
     for name in ("kv_init", "kv_step", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_timing",
-                 "kv_read_timing", "kv_set_option"):
+                 "kv_read_timing", "kv_set_option", "kv_probe_mfma_bf16", "kv_probe_copy"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
+
+
+def probe_mfma_bf16(iters: int = 50000, repeats: int = 3, hip_stream: int = 0) -> float:
+    """kv_probe_mfma_bf16: TFLOP/s of a register-resident bf16 matrix-instruction loop on every compute unit."""
+    out = C.c_double(0.0)
+    rc = load_library().kv_probe_mfma_bf16(iters, repeats, hip_stream, C.byref(out))
+    if rc != 0:
+        raise KvError(rc, "kv_probe_mfma_bf16 failed")
+    return out.value
+
+
+def probe_copy(nbytes: int = 1 << 30, repeats: int = 3, hip_stream: int = 0) -> float:
+    """kv_probe_copy: GB/s (read + written) of a streaming device-to-device copy of nbytes bytes."""
+    out = C.c_double(0.0)
+    rc = load_library().kv_probe_copy(nbytes, repeats, hip_stream, C.byref(out))
+    if rc != 0:
+        raise KvError(rc, "kv_probe_copy failed")
+    return out.value
 
 
 class KvHandle:

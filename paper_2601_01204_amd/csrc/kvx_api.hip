@@ -242,7 +242,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   const int64_t n_caches = (int64_t)c.n_streams * c.n_layers;
   h->caches.assign((size_t)n_caches, CacheState());
   h->slots_cap = 0;
-  for (int items = 1; items <= kMaxItems; ++items) {
+  for (int items = 1; items <= std::min<int64_t>(kMaxItems, n_caches); ++items) {
     // the most splits pick_splits can choose for this many items with 256 target workgroups
     const int64_t base = (int64_t)items * g.H * g.n_qtiles;
     const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, 512 / base));

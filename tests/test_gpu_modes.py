@@ -203,3 +203,18 @@ def test_step_argument_errors_leave_the_cache_untouched():
     torch.cuda.synchronize()
     assert h.stats()["frames_seen_total"] == 1
     h.close()
+
+
+def test_machine_probes_report_plausible_rates():
+    """kv_probe_mfma_bf16 / kv_probe_copy: positive rates below the published peaks; bad arguments rejected."""
+    import ctypes as C
+    import paper_2601_01204_amd as kvx
+    t = kvx.probe_mfma_bf16(2000, 2)
+    assert 100.0 < t < 2600.0, t
+    g = kvx.probe_copy(64 << 20, 2)
+    assert 200.0 < g < 8500.0, g
+    out = C.c_double(0.0)
+    lib = kvx.load_library()
+    assert lib.kv_probe_mfma_bf16(0, 1, None, C.byref(out)) == -1
+    assert lib.kv_probe_copy(100, 1, None, C.byref(out)) == -1
+    assert lib.kv_probe_copy(1 << 20, 1, None, None) == -1
