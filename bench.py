@@ -120,6 +120,16 @@ def aux_measurements(torch, kvx, si, dev, frames, peak_hbm):
         us = ms * 1e3 / cnt
         gbs = NL * nbytes / (us * 1e-6) / 1e9
         hb[name] = {"us": round(us, 2), "GB/s": round(gbs, 1), "frac": round(gbs / peak_hbm, 4)}
+    # score and key rebuild are bound by vector-instruction issue, not memory: instructions per wave from
+    # rocprofv3 SQ_INSTS_VALU / SQ_WAVES (profiles/update_kernels_vggt_stack_counters.txt, INT4 kernels), one wave
+    # per 64 cached tokens and head (score) or per 16 tokens and head (rebuild), against the chip's issue rate of
+    # one 64-lane instruction per SIMD every 4 cycles: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instr/s
+    if kb == 4:
+        peak_lane_instr = 256 * 4 * 16 * 2.4e9
+        for name, per_wave, waves in (("score", 413.25, NL * H * (L // 64)), ("rebuild_k", 340.4, NL * H * (L // 16))):
+            rate = per_wave * waves * 64 / (hb[name]["us"] * 1e-6)
+            hb[name]["valu"] = {"bound": "alu", "achieved": round(rate / 1e12, 2), "peak": round(peak_lane_instr / 1e12, 2),
+                                "unit": "T lane-instr/s", "frac": round(rate / peak_lane_instr, 4)}
     ms, cnt = tm["attention"]
     us = ms * 1e3 / cnt
     out["stack24_batched_step"] = {
