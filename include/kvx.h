@@ -94,7 +94,11 @@ typedef struct kv_stats_t {
   int32_t cache_len_min;         /* over caches                                                  */
   int32_t cache_len_max;
   int32_t n_caches;
-  int32_t reserved;
+  int32_t nonfinite_flag;        /* 1 if a step with "debug_checks" on met an infinity or NaN in  */
+                                 /* q, k or v since kv_init (the step itself ran unchanged)       */
+  int64_t zp_range_warnings;     /* quantisation groups written since kv_init whose zero-point    */
+                                 /* lies beyond +-2^20: their values sit so far from zero,        */
+                                 /* measured in quantisation steps, that Eq. 10 cancels most bits */
 } kv_stats_t;
 
 /* Host buffers for kv_export; any pointer may be NULL to skip that part. Sizes are in
@@ -148,6 +152,16 @@ int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* bufs);
 /* Forget the contents of one cache (stream, layer), or of all with stream = layer = -1. */
 int kv_reset(kv_handle* h, int32_t stream, int32_t layer);
 
+/* Load a cache from host buffers laid out as kv_export writes them (the checkpoint of a
+ * stream: Sec. 3.2 bounds the state by L_max tokens, so this is all a stream needs to resume).
+ * bufs: host; cache_len, frames_seen, ids, k_codes, k_scale, k_zero, v_codes, v_scale and
+ * v_zero must be set, with cache_len = min(frames_seen * tokens_per_frame, budget_tokens) and
+ * every code below 2^bits; last_keep and last_scores are ignored.  Waits for the device, then
+ * replaces the cache of (stream, layer); the next kv_step continues the stream exactly as the
+ * exporting handle would have.  KV_E_STATE in KV_UNCOMPRESSED_BF16 mode, KV_E_INVAL / KV_E_RANGE
+ * for inconsistent buffers (the cache is then left as it was). */
+int kv_import(kv_handle* h, int32_t stream, int32_t layer, const kv_export_t* bufs);
+
 /* Free everything.  NULL is allowed. */
 void kv_destroy(kv_handle* h);
 
@@ -177,6 +191,8 @@ int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches);
 /* Tuning knobs (not needed for correct results):
  *   "attention_splits"            0 = choose automatically, 1..16 = key-range splits
  *   "attention_target_workgroups" workgroups the automatic choice aims for
+ *   "debug_checks"                1: every step first scans q, k and v for infinities and NaNs
+ *                                 and reports them through kv_stats (nonfinite_flag); 0 (default)
  *   "overlap_update"              1 (default): scoring, pruning and re-quantisation run on a
  *                                 second stream of the library beside attention, joined back
  *                                 into hip_stream before kv_step returns; 0: everything in

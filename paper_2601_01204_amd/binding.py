@@ -32,10 +32,11 @@ class KvStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "bytes_allocated", "bytes_k_codes", "bytes_k_meta", "bytes_v_codes", "bytes_v_meta", "bytes_ids",
         "bytes_scratch", "bytes_live_per_cache", "frames_seen_total", "tokens_dropped_total",
-        "k_groups_rebuilt_total")] + [(n, C.c_int32) for n in ("cache_len_min", "cache_len_max", "n_caches", "reserved")]
+        "k_groups_rebuilt_total")] + [(n, C.c_int32) for n in ("cache_len_min", "cache_len_max", "n_caches", "nonfinite_flag")] + [
+        ("zp_range_warnings", C.c_int64)]
 
     def as_dict(self):
-        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+        return {n: getattr(self, n) for n, _ in self._fields_}
 
 
 class KvExport(C.Structure):
@@ -70,6 +71,7 @@ def load_library():
     lib.kv_stats.argtypes = [P, C.POINTER(KvStats)]
     lib.kv_export.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(KvExport)]
     lib.kv_reset.argtypes = [P, C.c_int32, C.c_int32]
+    lib.kv_import.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(KvExport)]
     lib.kv_destroy.argtypes = [P]
     lib.kv_destroy.restype = None
     lib.kv_last_error.argtypes = [P]
@@ -80,7 +82,7 @@ def load_library():
     lib.kv_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, P, C.POINTER(C.c_double)]
     lib.kv_probe_copy.argtypes = [C.c_int64, C.c_int32, P, C.POINTER(C.c_double)]
     for name in ("kv_init", "kv_step", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_timing",
-                 "kv_read_timing", "kv_set_option", "kv_probe_mfma_bf16", "kv_probe_copy"):
+                 "kv_read_timing", "kv_set_option", "kv_probe_mfma_bf16", "kv_probe_copy", "kv_import"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -185,6 +187,22 @@ class KvHandle:
         out["last_keep"] = bufs["last_keep"][:x.last_keep_len].copy() if x.last_keep_len else None
         out["last_scores"] = bufs["last_scores"][:x.last_scores_len].copy() if x.last_keep_len else None
         return out
+
+    def import_state(self, state: dict, stream: int = 0, layer: int = 0):
+        """kv_import: load what export() returned (of this or another handle with the same configuration)."""
+        arrs = dict(ids=(np.int32, state["ids"]), k_codes=(np.uint8, state["k_codes"]), k_scale=(np.float32, state["k_scale"]),
+                    k_zero=(np.int32, state["k_zero"]), v_codes=(np.uint8, state["v_codes"]),
+                    v_scale=(np.float32, state["v_scale"]), v_zero=(np.int32, state["v_zero"]))
+        x = KvExport()
+        x.cache_len = int(state["cache_len"])
+        x.frames_seen = int(state["frames_seen"])
+        x.capacity_tokens = x.cache_len
+        keep = []
+        for name, (dt, a) in arrs.items():
+            a = np.ascontiguousarray(a, dtype=dt)
+            keep.append(a)
+            setattr(x, name, a.ctypes.data)
+        self._check(self.lib.kv_import(self._h, stream, layer, C.byref(x)))
 
     def reset(self, stream: int = -1, layer: int = -1):
         self._check(self.lib.kv_reset(self._h, stream, layer))

@@ -57,6 +57,7 @@ struct kv_handle {
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   int32_t overlap = 1;
+  int32_t debug_checks = 0;
   std::string err;
   // timing
   uint32_t timing_mask = 0;
@@ -378,6 +379,7 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
       launch_rebuild_v(b, max_tnew, sb);
       record(h, KV_K_REBUILD_V, false, sb);
     }
+    if (h->debug_checks) launch_check_finite(b, st);
     {
       // the attention kernel is timed by events the runtime stamps at the kernel's own start
       // and end, so the figure is the kernel's duration as a kernel trace reports it
@@ -450,10 +452,12 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
     mn = std::min(mn, cs.t_c);
     mx = std::max(mx, cs.t_c);
     if (!g.uncompressed) {
-      int32_t sel[4];
+      int32_t sel[8];
       if (hipMemcpy(sel, h->scratch + (int64_t)i * g.sl.bytes + g.sl.sel, sizeof sel, hipMemcpyDeviceToHost) != hipSuccess)
         return fail(h, KV_E_HIP, "kv_stats: %s", hipGetErrorString(hipGetLastError()));
       s->k_groups_rebuilt_total += sel[2];
+      s->zp_range_warnings += sel[5];
+      s->nonfinite_flag |= sel[6] != 0;
     }
   }
   s->cache_len_min = mn;
@@ -529,6 +533,69 @@ int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* x) {
   return KV_OK;
 }
 
+int kv_import(kv_handle* h, int32_t stream, int32_t layer, const kv_export_t* x) {
+  if (!h) return KV_E_INVAL;
+  if (!x) return fail(h, KV_E_INVAL, "kv_import: bufs is NULL");
+  const kv_config& c = h->cfg;
+  if (stream < 0 || stream >= c.n_streams || layer < 0 || layer >= c.n_layers) return fail(h, KV_E_RANGE, "kv_import: stream/layer out of range");
+  const Geometry& g = h->geo;
+  if (g.uncompressed) return fail(h, KV_E_STATE, "kv_import: not available in KV_UNCOMPRESSED_BF16 mode");
+  if (!x->ids || !x->k_codes || !x->k_scale || !x->k_zero || !x->v_codes || !x->v_scale || !x->v_zero)
+    return fail(h, KV_E_INVAL, "kv_import: ids, codes, scales and zero-points must all be given");
+  const int T = x->cache_len;
+  if (x->frames_seen < 0 || T < 0 || T > g.budget) return fail(h, KV_E_RANGE, "kv_import: cache_len %d / frames_seen %d out of range", T, x->frames_seen);
+  if ((int64_t)T != std::min<int64_t>((int64_t)x->frames_seen * g.n, g.budget))
+    return fail(h, KV_E_INVAL, "kv_import: cache_len %d is not min(frames_seen * tokens_per_frame, budget_tokens)", T);
+  const int H = g.H;
+  const int G = (T + g.k_group - 1) / g.k_group;
+  const int ngv = kHeadDim / g.v_group;
+  // pack the codes into rows of d * bits / 8 bytes, as the kernels store them
+  auto pack = [&](const uint8_t* src, int bits, std::vector<uint8_t>& dst) -> bool {
+    const int row = kHeadDim * bits / 8;
+    dst.assign((size_t)H * T * row, 0);
+    for (int64_t r = 0; r < (int64_t)H * T; ++r)
+      for (int ch = 0; ch < kHeadDim; ++ch) {
+        const uint8_t code = src[r * kHeadDim + ch];
+        if (code >> bits) return false;
+        const int bit = ch * bits;
+        dst[(size_t)r * row + (bit >> 3)] |= (uint8_t)(code << (bit & 7));
+      }
+    return true;
+  };
+  std::vector<uint8_t> kc, vc;
+  if (!pack(x->k_codes, g.k_bits, kc)) return fail(h, KV_E_INVAL, "kv_import: a key code does not fit %d bits", g.k_bits);
+  if (!pack(x->v_codes, g.v_bits, vc)) return fail(h, KV_E_INVAL, "kv_import: a value code does not fit %d bits", g.v_bits);
+  std::vector<VMeta> vm((size_t)H * T * ngv);
+  for (size_t i = 0; i < vm.size(); ++i) {
+    vm[i].s = x->v_scale[i];
+    vm[i].z = x->v_zero[i];
+  }
+  if (hipDeviceSynchronize() != hipSuccess) return fail(h, KV_E_HIP, "kv_import: %s", hipGetErrorString(hipGetLastError()));
+  const size_t ci = (size_t)stream * c.n_layers + layer;
+  uint8_t* half = h->arena + (int64_t)ci * g.lay.cache_bytes;        // the cache restarts in its first half
+  auto h2d = [&](void* dst, const void* src, size_t bytes) { return bytes == 0 || hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice) == hipSuccess; };
+  bool ok = h2d(half + g.lay.ids, x->ids, (size_t)T * 4);
+  const int krow = kHeadDim * g.k_bits / 8, vrow = kHeadDim * g.v_bits / 8;
+  for (int hh = 0; hh < H && ok; ++hh) {
+    ok &= h2d(half + g.lay.k_codes + (int64_t)hh * g.t_cap * krow, kc.data() + (size_t)hh * T * krow, (size_t)T * krow);
+    ok &= h2d(half + g.lay.v_codes + (int64_t)hh * g.t_cap * vrow, vc.data() + (size_t)hh * T * vrow, (size_t)T * vrow);
+    ok &= h2d(half + g.lay.k_scale + (int64_t)hh * g.g_cap * kHeadDim * 4, x->k_scale + (int64_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 4);
+    ok &= h2d(half + g.lay.k_zero + (int64_t)hh * g.g_cap * kHeadDim * 4, x->k_zero + (int64_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 4);
+    ok &= h2d(half + g.lay.v_meta + (int64_t)hh * g.t_cap * ngv * sizeof(VMeta), vm.data() + (size_t)hh * T * ngv, (size_t)T * ngv * sizeof(VMeta));
+  }
+  if (!ok) {
+    h->caches[ci] = CacheState();       // partly written: the cache is empty rather than inconsistent
+    return fail(h, KV_E_HIP, "kv_import: copy failed: %s", hipGetErrorString(hipGetLastError()));
+  }
+  CacheState cs;
+  cs.t_c = T;
+  cs.cur = 0;
+  cs.frames = x->frames_seen;
+  cs.dropped = (int64_t)x->frames_seen * g.n - T;
+  h->caches[ci] = cs;
+  return KV_OK;
+}
+
 int kv_reset(kv_handle* h, int32_t stream, int32_t layer) {
   if (!h) return KV_E_INVAL;
   const kv_config& c = h->cfg;
@@ -587,6 +654,10 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
   if (!strcmp(name, "attention_splits")) {
     if (value < 0 || value > kMaxSplits) return fail(h, KV_E_RANGE, "kv_set_option: attention_splits must be in [0, %d]", (int)kMaxSplits);
     h->splits_override = (int32_t)value;
+    return KV_OK;
+  }
+  if (!strcmp(name, "debug_checks")) {
+    h->debug_checks = value != 0;
     return KV_OK;
   }
   if (!strcmp(name, "overlap_update")) {

@@ -38,7 +38,7 @@ struct ScratchLayout {
   int64_t scores;     // [t_cap] float: importance score of middle tokens (index = cache position - n)
   int64_t keys;       // [t_cap] uint32: order-preserving image of the scores
   int64_t keep;       // [t_cap] int32: kept positions, ascending
-  int64_t sel;        // [16] int32: [0] first dropped position, [1] first rebuilt key group, [2] groups rebuilt (running), [3] kept middle tokens, [4] pooled-row blocks finished
+  int64_t sel;        // [16] int32: [0] first dropped position, [1] first rebuilt key group, [2] groups rebuilt (running), [3] kept middle tokens, [5] groups quantised with a zero-point beyond +-2^20 (running), [6] non-finite input seen (debug checks)
   int64_t bytes;
 };
 
@@ -110,5 +110,8 @@ void launch_select(const KvxBatch& b, int max_tc, hipStream_t st);
 void launch_rebuild_k(const KvxBatch& b, int max_tnew, hipStream_t st);
 void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st);
 void launch_append_bf16(const KvxBatch& b, hipStream_t st);
+void launch_check_finite(const KvxBatch& b, hipStream_t st);
+
+constexpr int32_t kZeroPointWarn = 1 << 20;   // |z| beyond this is counted by kv_stats (zp_range_warnings)
 
 }  // namespace kvx

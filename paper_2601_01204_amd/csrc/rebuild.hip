@@ -250,6 +250,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
         }
         quant_params(mn, mx, levels, s, z);
         if (h == 0 && c == 0) atomicAdd(&sel[2], 1);
+        if (z > kZeroPointWarn || z < -kZeroPointWarn) atomicAdd(&sel[5], 1);
       }
       const Divider dv = make_divider(s);
       gs[gi][c] = s;
@@ -373,6 +374,8 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_
   for (int e = 0; e < 16; ++e) code[e] = quant_code_div(x[e], dv, z, levels);
   pack16<B>(code, nxt + g.lay.v_codes + ((int64_t)h * g.t_cap + p) * kRow + cb * 2 * B);
   if ((cb % lanes_per_group) == 0) {
+    if (z > kZeroPointWarn || z < -kZeroPointWarn)
+      atomicAdd(reinterpret_cast<int32_t*>(cache_scratch(g, it.cache) + g.sl.sel) + 5, 1);
     VMeta m;
     m.s = s;
     m.z = z;

@@ -218,3 +218,83 @@ def test_machine_probes_report_plausible_rates():
     assert lib.kv_probe_mfma_bf16(0, 1, None, C.byref(out)) == -1
     assert lib.kv_probe_copy(100, 1, None, C.byref(out)) == -1
     assert lib.kv_probe_copy(1 << 20, 1, None, None) == -1
+
+
+def test_import_resumes_a_stream_bit_for_bit():
+    """kv_export -> kv_import into a second handle: both continue the stream with identical outputs
+    and cache states (the checkpoint holds everything a stream needs), and both still match the oracle."""
+    import torch
+    w = _small(frames=12)
+    a = pu.make_handle(w)
+    cache = xo.OracleCache(pu.oracle_cfg(w))
+    sigma = si.key_channel_scales(w)
+    frames = [si.frame_qkv(w, t, sigma=sigma) for t in range(12)]
+
+    def feed(h, t):
+        tq, tk, tv = (pu.to_device(x, w) for x in frames[t])
+        out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+        h.step(tq, tk, tv, out)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    for t in range(8):                       # past pruning onset
+        feed(a, t)
+        cache.step(*frames[t])
+    snap = a.export()
+    b = pu.make_handle(w)
+    b.import_state(snap)
+    again = b.export()
+    for name in ("ids", "k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero"):
+        assert np.array_equal(snap[name].view(np.uint8), again[name].view(np.uint8)), name
+    assert again["frames_seen"] == 8 and again["cache_len"] == snap["cache_len"]
+    for t in range(8, 12):
+        oa, ob = feed(a, t), feed(b, t)
+        ref = cache.step(*frames[t])
+        assert np.array_equal(oa.view(np.uint32), ob.view(np.uint32)), f"frame {t}: outputs differ after import"
+        pu.check_output(ob, ref, f"imported frame {t}")
+        pu.check_state(b.export(), cache, f"imported frame {t}")
+    # inconsistent buffers are refused and leave the cache as it was
+    bad = dict(snap)
+    bad["frames_seen"] = 1
+    with pytest.raises(kvx_mod().KvError) as e:
+        b.import_state(bad)
+    assert e.value.code == -1
+    bad = dict(snap)
+    bad["k_codes"] = snap["k_codes"].copy()
+    bad["k_codes"][0, 0, 0] = 255
+    with pytest.raises(kvx_mod().KvError):
+        b.import_state(bad)
+    pu.check_state(b.export(), cache, "after refused imports")
+    a.close()
+    b.close()
+
+
+def kvx_mod():
+    import paper_2601_01204_amd as kvx
+    return kvx
+
+
+def test_debug_checks_and_zero_point_warnings():
+    """With "debug_checks" on, a NaN in k raises kv_stats' nonfinite_flag (clean inputs do not); a key channel far
+    from zero in units of its range is counted in zp_range_warnings."""
+    import torch
+    w = _small(frames=4, dtype="f32")        # fp32 inputs: a range of 2^-9 at an offset of 2^12 needs 22 significant bits
+    h = pu.make_handle(w)
+    h.set_option("debug_checks", 1)
+    sigma = si.key_channel_scales(w)
+    q, k, v = si.frame_qkv(w, 0, sigma=sigma)
+    tq, tk, tv = (pu.to_device(x, w) for x in (q, k, v))
+    out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+    h.step(tq, tk, tv, out)
+    st = h.stats()
+    assert st["nonfinite_flag"] == 0 and st["zp_range_warnings"] == 0
+    k2 = k.copy()
+    k2[:, 0, 3] = 4096.0 + 2.0 ** -9 * (np.arange(k.shape[0]) % 2)      # z = -4096 * 15 * 512, far beyond 2^20
+    h.step(tq, pu.to_device(k2, w), tv, out)
+    st = h.stats()
+    assert st["nonfinite_flag"] == 0 and st["zp_range_warnings"] > 0
+    k3 = k.copy()
+    k3[5, 1, 7] = np.nan
+    h.step(tq, pu.to_device(k3, w), tv, out)
+    assert h.stats()["nonfinite_flag"] == 1
+    h.close()

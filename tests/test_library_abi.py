@@ -14,14 +14,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "kvx.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(kv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(kv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():
     lib = kvx.load_library()
     names = _declared_functions()
     assert {"kv_init", "kv_step", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_destroy",
-            "kv_last_error", "kv_set_timing", "kv_read_timing", "kv_set_option"} <= set(names)
+            "kv_last_error", "kv_set_timing", "kv_read_timing", "kv_set_option", "kv_import", "kv_probe_mfma_bf16",
+            "kv_probe_copy"} <= set(names)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in kvx.h but not exported by libkvx.so"
 
@@ -74,6 +75,7 @@ def test_null_arguments():
     lib.kv_destroy(None)                      # allowed
     assert lib.kv_stats(None, None) == -1
     assert lib.kv_reset(None, 0, 0) == -1
+    assert lib.kv_import(None, 0, 0, None) == -1
     assert lib.kv_step(None, 0, 0, None, None, None, 64, 64, None, None) == -1
 
 
