@@ -212,3 +212,65 @@ def test_bf16_inputs_are_representable():
     # a few key channels dominate
     sig = si.key_channel_scales(w)
     assert sig.max() / np.median(sig) > 5
+
+
+def test_kept_ids_recomputed_from_the_printed_equations():
+    """Pruning only (quant off): after every pruning step the cache holds exactly the first frame, the current
+    frame and the k best of the tokens in between, with the scores recomputed here from Eq. 2-6 as printed
+    (pooled query per head, head means of query and key, N_pooled x M product, column means) on the true keys
+    of the tokens the cache held, addressed by id."""
+    cfg = _small_cfg(quant=False, budget_tokens=37)
+    fr = _frames(cfg, 9, seed=21)
+    n, ns, g = cfg.tokens_per_frame, cfg.n_special, cfg.pool_group
+    all_k = np.concatenate([f[1] for f in fr], axis=0).astype(np.float64)      # [frames * n, H, d] by token id
+    cache = xo.OracleCache(cfg)
+    pruned = 0
+    for t, (q, k, v) in enumerate(fr):
+        ids_before = cache.ids.copy()
+        cache.step(q, k, v)
+        ids = np.concatenate([ids_before, t * n + np.arange(n)])
+        T = len(ids)
+        if T <= cfg.budget_tokens:
+            assert np.array_equal(cache.ids, ids)
+            continue
+        pruned += 1
+        q64 = q.astype(np.float64)
+        rows = [q64[i] for i in range(ns)]                                       # Eq. 2: [H, d] per pooled row
+        a = ns
+        while a < n:
+            rows.append(q64[a:min(a + g, n)].mean(axis=0))
+            a += g
+        q_bar = np.stack(rows).mean(axis=1)                                      # Eq. 3: [N_pooled, d]
+        mid_ids = ids[n:T - n]
+        k_bar = all_k[mid_ids].mean(axis=1)                                      # Eq. 4: [M, d]
+        s = (q_bar @ k_bar.T).mean(axis=0)                                       # Eq. 5-6: [M]
+        kk = cfg.budget_tokens - 2 * n
+        order = np.argsort(-s, kind="stable")
+        best = np.sort(order[:kk])
+        margin = s[order[kk - 1]] - s[order[kk]]
+        assert margin > 1e-4 * np.abs(s).max(), "near-tie in the test data: pick another seed"
+        expect = np.concatenate([ids[:n], mid_ids[best], ids[T - n:]])
+        assert np.array_equal(cache.ids, expect), f"frame {t}"
+    assert pruned >= 5
+
+
+def test_every_stored_key_follows_its_own_token():
+    """A token's stored key moves by at most half a quantisation step of its new group whenever its group is
+    rebuilt, and not at all when the group is carried: followed by token id across compaction, so codes or
+    metadata left behind for a group whose members changed would show."""
+    cfg = _small_cfg(k_bits=4, v_bits=4, budget_tokens=41)
+    fr = _frames(cfg, 9, seed=22)
+    n, G = cfg.tokens_per_frame, cfg.k_group
+    cache = xo.OracleCache(cfg)
+    value = {}                                   # token id -> its key as last stored, [H, d]
+    for t, (q, k, v) in enumerate(fr):
+        for i in range(n):
+            value[t * n + i] = k[i].astype(np.float32)
+        cache.step(q, k, v)
+        stored = cache.stored_k()                # [H, T, d]
+        grp = np.arange(cache.cache_len) // G
+        step = cache.Ks[:, grp, :]
+        for pos, tid in enumerate(cache.ids):
+            prev = value[int(tid)]
+            assert np.all(np.abs(stored[:, pos, :] - prev) <= 0.5 * step[:, pos, :] * (1 + 1e-4) + 1e-30), (t, pos, int(tid))
+            value[int(tid)] = stored[:, pos, :].copy()
