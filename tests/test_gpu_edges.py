@@ -80,3 +80,57 @@ def test_reset_restarts_a_stream():
     assert h.stats()["cache_len_max"] == 0
     pu.run_stream(w, 5, handle=h)
     h.close()
+
+
+@pytest.mark.parametrize("n,n_special,g", [(20, 20, 4), (37, 5, 64), (33, 0, 33)])
+def test_pooling_extremes(n, n_special, g):
+    """Every token special (no pooled group at all), one short group that holds all patch tokens,
+    and one group of exactly all tokens."""
+    w = si.Workload(f"pool{n}_{n_special}_{g}", 2, 64, n, n_special, g, 4 * n + 7, 8, 1, 1, 4, 32, 4, 32, "bf16", 27)
+    pu.run_stream(w, 8)
+
+
+def test_two_handles_interleaved():
+    """Two handles of different shapes alive at once, stepped alternately on the same stream."""
+    wa = si.Workload("ha", 2, 64, 69, 5, 16, 200, 6, 1, 1, 4, 64, 4, 64, "bf16", 28)
+    wb = si.Workload("hb", 3, 64, 45, 3, 8, 150, 6, 1, 1, 8, 32, 2, 32, "f32", 29)
+    import torch
+    ha, hb = pu.make_handle(wa), pu.make_handle(wb)
+    ca, cb = xo.OracleCache(pu.oracle_cfg(wa)), xo.OracleCache(pu.oracle_cfg(wb))
+    sa, sb = si.key_channel_scales(wa), si.key_channel_scales(wb)
+    for t in range(6):
+        outs = []
+        for w, h, c, sg in ((wa, ha, ca, sa), (wb, hb, cb, sb)):
+            q, k, v = si.frame_qkv(w, t, sigma=sg)
+            ref = c.step(q, k, v)
+            tq, tk, tv = (pu.to_device(x, w) for x in (q, k, v))
+            out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+            h.step(tq, tk, tv, out)
+            outs.append((w, h, c, out, ref, (tq, tk, tv)))
+        torch.cuda.synchronize()
+        for w, h, c, out, ref, _ in outs:
+            pu.check_output(out.cpu().numpy(), ref, f"{w.name} frame {t}")
+            pu.check_state(h.export(), c, f"{w.name} frame {t}")
+    ha.close()
+    hb.close()
+
+
+def test_fp32_inputs_with_bf16_output():
+    """in_dtype fp32, out_dtype bf16: the output is the nearest-even bf16 of the fp32-output run."""
+    import torch
+    w = si.Workload("mixed", 2, 64, 50, 5, 16, 160, 5, 1, 1, 4, 64, 4, 64, "f32", 30)
+    h32 = pu.make_handle(w)
+    h16 = pu.make_handle(w, out_dtype=0)
+    sigma = si.key_channel_scales(w)
+    for t in range(5):
+        q, k, v = si.frame_qkv(w, t, sigma=sigma)
+        tq, tk, tv = (pu.to_device(x, w) for x in (q, k, v))
+        o32 = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+        o16 = torch.empty(tq.shape, dtype=torch.bfloat16, device=tq.device)
+        h32.step(tq, tk, tv, o32)
+        # out shares the element strides of q: a bf16 [n, H, d] tensor has the same strides in elements
+        h16.step(tq, tk, tv, o16)
+        torch.cuda.synchronize()
+        assert torch.equal(o32.to(torch.bfloat16), o16), f"frame {t}"
+    h32.close()
+    h16.close()
