@@ -191,6 +191,9 @@ int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches);
 /* Tuning knobs (not needed for correct results):
  *   "attention_splits"            0 = choose automatically, 1..16 = key-range splits
  *   "attention_target_workgroups" workgroups the automatic choice aims for
+ *   "timing_every"                n >= 1 (default 1): kv_set_timing brackets the launches of every n-th
+ *                                 step call only; the event pairs cost a few microseconds of stream
+ *                                 time each, so a benchmark samples them rather than paying them per step
  *   "debug_checks"                1: every step first scans q, k and v for infinities and NaNs
  *                                 and reports them through kv_stats (nonfinite_flag); 0 (default)
  *   "overlap_update"              1 (default): scoring, pruning and re-quantisation run on a

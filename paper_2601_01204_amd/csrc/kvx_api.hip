@@ -61,6 +61,9 @@ struct kv_handle {
   std::string err;
   // timing
   uint32_t timing_mask = 0;
+  int32_t timing_every = 1;     // bracket the launches of every n-th kv_step / kv_step_batched call only
+  int64_t step_calls = 0;
+  bool timing_now = false;      // this call is one of them
   std::vector<TimedLaunch> timed;
   std::vector<TimedLaunch> free_events;
 };
@@ -136,7 +139,7 @@ int pick_splits(const kv_handle* h, int n_items, int min_tiles) {
 }
 
 void record(kv_handle* h, int kernel, bool start, hipStream_t st) {
-  if (!(h->timing_mask & (1u << kernel))) return;
+  if (!h->timing_now || !(h->timing_mask & (1u << kernel))) return;
   if (start) {
     TimedLaunch t;
     if (!h->free_events.empty()) {
@@ -159,7 +162,7 @@ void record(kv_handle* h, int kernel, bool start, hipStream_t st) {
 // An event pair for a launch that stamps its own events (nothing is recorded here).
 void timed_pair(kv_handle* h, int kernel, hipEvent_t* start, hipEvent_t* stop) {
   *start = *stop = nullptr;
-  if (!(h->timing_mask & (1u << kernel))) return;
+  if (!h->timing_now || !(h->timing_mask & (1u << kernel))) return;
   TimedLaunch t;
   if (!h->free_events.empty()) {
     t = h->free_events.back();
@@ -317,6 +320,8 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
       return fail(h, KV_E_STATE, "kv_step: cache (stream %d, layer %d) already holds max_frames frames", it.stream, it.layer);
   }
   hipStream_t st = (hipStream_t)hip_stream;
+  h->timing_now = h->timing_mask != 0 && (h->step_calls % h->timing_every) == 0;
+  h->step_calls += 1;
 
   for (int base = 0; base < n_items; base += kMaxItems) {
     const int cnt = std::min<int>(kMaxItems, n_items - base);
@@ -654,6 +659,11 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
   if (!strcmp(name, "attention_splits")) {
     if (value < 0 || value > kMaxSplits) return fail(h, KV_E_RANGE, "kv_set_option: attention_splits must be in [0, %d]", (int)kMaxSplits);
     h->splits_override = (int32_t)value;
+    return KV_OK;
+  }
+  if (!strcmp(name, "timing_every")) {
+    if (value < 1 || value > (1 << 20)) return fail(h, KV_E_RANGE, "kv_set_option: timing_every must be in [1, 2^20]");
+    h->timing_every = (int32_t)value;
     return KV_OK;
   }
   if (!strcmp(name, "debug_checks")) {
