@@ -298,3 +298,27 @@ def test_debug_checks_and_zero_point_warnings():
     h.step(tq, pu.to_device(k3, w), tv, out)
     assert h.stats()["nonfinite_flag"] == 1
     h.close()
+
+
+def test_timing_can_be_sampled():
+    """kv_set_timing brackets every launch of the chosen classes, or those of every n-th step with "timing_every"."""
+    import torch
+    w = _small(frames=8)
+    h = pu.make_handle(w)
+    sigma = si.key_channel_scales(w)
+    tq, tk, tv = (pu.to_device(x, w) for x in si.frame_qkv(w, 0, sigma=sigma))
+    out = torch.empty(tq.shape, dtype=torch.float32, device=tq.device)
+    h.set_timing(1 | (1 << 5))                 # attention and key rebuild
+    for _ in range(8):
+        h.step(tq, tk, tv, out)
+    tm = h.read_timing()
+    assert tm["attention"][1] == 8 and tm["rebuild_k"][1] == 8 and tm["score"][1] == 0
+    assert tm["attention"][0] > 0.0
+    h.set_option("timing_every", 4)
+    for _ in range(8):
+        h.step(tq, tk, tv, out)
+    tm = h.read_timing()
+    assert tm["attention"][1] == 2 and tm["rebuild_k"][1] == 2
+    with pytest.raises(kvx_mod().KvError):
+        h.set_option("timing_every", 0)
+    h.close()
