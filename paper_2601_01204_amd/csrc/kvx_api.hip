@@ -50,6 +50,7 @@ struct kv_handle {
   int64_t bytes_arena = 0, bytes_scratch = 0, bytes_part = 0;
   int32_t slots_cap = 0;
   int32_t splits_override = 0;
+  int32_t n_cus = 256;        // compute units of the device (an attention workgroup occupies one by itself)
   int32_t target_wgs = 192;   // three quarters of the CUs: the rest runs the cache-update chain beside attention
   int device = 0;
   // second stream for the score / prune / re-quantise chain, which is independent of the
@@ -243,13 +244,23 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   S.sel = off;    off = align_up(off + 64, 256);
   S.bytes = off;
 
+  int cus = 0;
+  if (hipGetDevice(&h->device) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device) != hipSuccess || cus < 1) {
+    rc = fail(nullptr, KV_E_HIP, "kv_init: no HIP device: %s", hipGetErrorString(hipGetLastError()));
+    delete h;
+    return rc;
+  }
+  h->n_cus = cus;
+  h->target_wgs = std::max(1, cus * 3 / 4);
+
   const int64_t n_caches = (int64_t)c.n_streams * c.n_layers;
   h->caches.assign((size_t)n_caches, CacheState());
   h->slots_cap = 0;
   for (int items = 1; items <= std::min<int64_t>(kMaxItems, n_caches); ++items) {
-    // the most splits pick_splits can choose for this many items with 256 target workgroups
+    // the most splits pick_splits can choose for this many items when it aims at every compute unit
     const int64_t base = (int64_t)items * g.H * g.n_qtiles;
-    const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, 512 / base));
+    const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, 2 * (int64_t)cus / base));
     h->slots_cap = std::max(h->slots_cap, items * cap);
   }
   h->slots_cap = std::max(h->slots_cap, (int32_t)kMaxSplits);
@@ -259,11 +270,6 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   const int64_t part_ml_bytes = (int64_t)h->slots_cap * g.H * g.n_pad * 2 * 4;
   h->bytes_part = part_o_bytes + part_ml_bytes;
 
-  if (hipGetDevice(&h->device) != hipSuccess) {
-    rc = fail(nullptr, KV_E_HIP, "kv_init: no HIP device: %s", hipGetErrorString(hipGetLastError()));
-    delete h;
-    return rc;
-  }
   hipError_t e1 = hipMalloc((void**)&h->arena, (size_t)h->bytes_arena);
   hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&h->scratch, (size_t)h->bytes_scratch) : e1;
   hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&h->part_o, (size_t)part_o_bytes) : e2;
@@ -672,7 +678,7 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
   }
   if (!strcmp(name, "overlap_update")) {
     h->overlap = value != 0;
-    h->target_wgs = h->overlap ? 192 : 256;
+    h->target_wgs = h->overlap ? std::max(1, h->n_cus * 3 / 4) : h->n_cus;
     return KV_OK;
   }
   if (!strcmp(name, "attention_target_workgroups")) {
