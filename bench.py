@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the compressed-KV streaming attention step on one MI355X.
 
-A step is one kv_step() on the 'vggt_layer' workload (the benchmark's second configuration: one
-VGGT-scale global-attention layer, 16 heads x 64, 1041 tokens per frame, budget 8192,
-INT4 keys per channel / INT4 values per token, group 64) in steady state, i.e. with the
-cache full so that every step attends over 8192 + 1041 keys, scores, prunes 1041 tokens
-and re-quantises.  Inputs are synthetic and resident in HBM before the timed region.
+A step is one frame of the 'vggt_stack' workload (the benchmark's third configuration, the one
+its work figures are quoted on): 24 independent per-layer caches of a VGGT-scale global-attention
+stack, 16 heads x 64, 1041 tokens per frame, budget 16384 tokens per layer, INT4 keys per channel /
+INT4 values per token, group 64, stepped by one kv_step_batched() call, in steady state (every cache
+full, so every layer attends over 16384 + 1041 keys, scores, prunes 1041 tokens and re-quantises).
+Inputs are synthetic, generated on the device and resident in HBM before the timed region.
 Prints one JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -22,164 +24,273 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
-# profiles/attn_kernel_vggt_layer_counters.txt), fetch counter scaled by 2.00, write by 1.00.
-ATTENTION_TRAFFIC_BYTES = 34.25e6
+# HBM bytes per launch of the dominant kernel come from a rocprofv3 --pmc run whose summary and figures are
+# tracked in profiles/; the file names the sources it was measured on, and a stale file yields traffic = null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attn_kernel_vggt_stack_traffic.json")
+KERNEL_SOURCES = ("attn.hip", "kvx_api.hip", "kvx_dev.h")
 
 
-def oracle_baseline(w, frames_total=18, steady_from=9):
-    """The CPU oracle as it stands, timed on this host: frames 0..frames_total-1 of the same
-    stream; the rate is taken over the steady frames (cache full, pruning every step)."""
+def kernel_source_hash() -> str:
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2601_01204_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def attention_traffic(workload: str, meta: str):
+    """HBM bytes per attention launch as the counters measured them, or None when the tracked figure
+    was taken on other sources or another workload."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if t.get("workload") != workload or t.get("metadata") != meta or t.get("source_sha256_16") != kernel_source_hash():
+        return None
+    return float(t["hbm_bytes_per_launch"])
+
+
+def device_frames(torch, w, dev, caches, ring, seed):
+    """ring distinct frames per cache, generated on the device: Q, V ~ N(0, 1), K ~ N(0, 1) times a
+    per-(cache, head, channel) log-normal scale, rounded to bf16 (the recipe of synth_inputs, drawn by
+    torch's device generator so that 24-96 caches x 20 frames need no host time)."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    n, H, d = w.tokens_per_frame, w.n_heads, w.head_dim
+    out = []
+    for _ in range(caches):
+        sigma = torch.exp(torch.randn((H, d), generator=gen, device=dev))
+        q = torch.randn((ring, n, H, d), generator=gen, device=dev).to(torch.bfloat16)
+        k = (torch.randn((ring, n, H, d), generator=gen, device=dev) * sigma).to(torch.bfloat16)
+        v = torch.randn((ring, n, H, d), generator=gen, device=dev).to(torch.bfloat16)
+        out.append((q, k, v))
+    return out
+
+
+def alg_bytes(w, meta_bytes=8):
+    """Algorithmic HBM bytes of the bandwidth kernels per cache-step in steady state (cache full)."""
+    n, H, d, L = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens
+    kb, vb = w.k_bits, w.v_bits
+    mid = L - n
+    k_meta = H * (L // w.k_group) * d * meta_bytes
+    v_meta = H * L * (d // w.v_group) * meta_bytes
+    return {
+        # middle key codes + their (s, z) read, D[h, j] written
+        "score": H * mid * d * kb / 8 + H * (mid // w.k_group) * d * meta_bytes + H * mid * 4,
+        # survivors' key codes + (s, z) read, new frame read, next cache written
+        "rebuild_k": 2 * (H * L * d * kb / 8 + k_meta) + n * H * d * 2,
+        "rebuild_v": 2 * (H * L * d * vb / 8 + v_meta) + n * H * d * 2,
+        "select": H * mid * 4 + 6 * mid * 4 + L * 4,
+    }
+
+
+def attention_flops(w):
+    n, H, d, L = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens
+    return 4.0 * n * (L + n) * d * H
+
+
+class StackRun:
+    """caches = n_streams x n_layers caches of workload w, all stepped by one kv_step_batched per frame."""
+
+    def __init__(self, torch, kvx, w, dev, n_streams, n_layers, ring, seed, **extra):
+        self.torch, self.w = torch, w
+        self.n_streams, self.n_layers = n_streams, n_layers
+        self.h = kvx.KvHandle(n_streams=n_streams, n_layers=n_layers, n_heads=w.n_heads, tokens_per_frame=w.tokens_per_frame,
+                              n_special=w.n_special, pool_group=w.pool_group, budget_tokens=w.budget_tokens, k_bits=w.k_bits,
+                              k_group=w.k_group, v_bits=w.v_bits, v_group=w.v_group, in_dtype=kvx.KV_BF16,
+                              out_dtype=kvx.KV_BF16, **extra)
+        nc = n_streams * n_layers
+        self.frames = device_frames(torch, w, dev, nc, ring, seed)
+        self.ring = ring
+        self.outs = [torch.empty((w.tokens_per_frame, w.n_heads, w.head_dim), dtype=torch.bfloat16, device=dev) for _ in range(nc)]
+        self.t = 0
+        self.stream = torch.cuda.current_stream().cuda_stream
+
+    def step(self):
+        r = self.t % self.ring
+        items = []
+        for s in range(self.n_streams):
+            for l in range(self.n_layers):
+                c = s * self.n_layers + l
+                q, k, v = self.frames[c]
+                items.append((s, l, q[r], k[r], v[r], self.outs[c]))
+        self.h.step_batched(items, hip_stream=self.stream)
+        self.t += 1
+
+    def run(self, steps):
+        for _ in range(steps):
+            self.step()
+
+    def timed(self, steps):
+        self.torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.run(steps)
+        self.torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def close(self):
+        self.h.close()
+
+
+def kernel_times(run, steps):
+    """Per-kernel durations with the cache update after attention on one stream (each kernel by itself)."""
+    run.h.set_option("overlap_update", 0)
+    run.h.set_option("timing_every", 1)
+    run.h.set_timing(0x7F)
+    run.run(steps)
+    run.torch.cuda.synchronize()
+    tm = run.h.read_timing()
+    run.h.set_timing(0)
+    run.h.set_option("overlap_update", 1)
+    return {k: v[0] * 1e3 / v[1] for k, v in tm.items() if v[1]}
+
+
+def hbm_report(w, n_caches_per_launch, us):
+    out = {}
+    for name, nbytes in alg_bytes(w).items():
+        if name in us:
+            gbs = n_caches_per_launch * nbytes / (us[name] * 1e-6) / 1e9
+            out[name] = {"us": round(us[name], 2), "bytes": int(n_caches_per_launch * nbytes), "GB/s": round(gbs, 1),
+                         "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    return out
+
+
+def oracle_baseline(torch, run, frames_total, steady):
+    """The CPU oracle as it stands, timed on this host on one layer cache of the same stream (the frames the GPU's
+    layer 0 was fed, copied back): frames 0..frames_total-1, the last `steady` of them with the cache full.  The
+    24-layer rate is one over 24 times the steady per-layer step time (the oracle's layers are independent)."""
     import numpy as np
-    import synth_inputs as si
     from oracle import xstream_oracle as xo
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
+    w = run.w
     cfg = xo.OracleConfig(w.n_heads, w.head_dim, w.tokens_per_frame, w.n_special, w.pool_group, w.budget_tokens,
                           w.k_bits, w.k_group, w.v_bits, w.v_group)
     cache = xo.OracleCache(cfg)
-    sigma = si.key_channel_scales(w)
-    steady = []
+    q, k, v = run.frames[0]
+    times = []
     for t in range(frames_total):
-        q, k, v = si.frame_qkv(w, t, sigma=sigma)
+        r = t % run.ring
+        fq, fk, fv = (a[r].float().cpu().numpy() for a in (q, k, v))
         t0 = time.perf_counter()
-        cache.step(q, k, v)
-        dt = time.perf_counter() - t0
-        if t >= steady_from:
-            steady.append(dt)
-    return {"value": len(steady) / sum(steady), "unit": "frames/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"frames 0-{frames_total - 1} of the same stream run through the numpy oracle; rate over steady frames "
-                      f"{steady_from}-{frames_total - 1} (cache full at {w.budget_tokens} tokens)"}
+        cache.step(fq, fk, fv)
+        times.append(time.perf_counter() - t0)
+    per_layer = sum(times[-steady:]) / steady
+    return {"value": 1.0 / (run.n_layers * per_layer), "unit": "frames/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"layer 0 of the same stream through the numpy oracle, frames 0-{frames_total - 1} ({sum(times):.1f} s of CPU "
+                      f"work); steady per-layer step {per_layer * 1e3:.0f} ms over the last {steady} frames (cache full at "
+                      f"{w.budget_tokens} tokens), times {run.n_layers} layers"}
 
 
-def aux_measurements(torch, kvx, si, dev, frames, peak_hbm):
-    """Side measurements, outside the timed region of the headline number:
-    (1) the attention kernel alone on the benchmark workload (no second stream, all CUs);
-    (2) one batched step over the 24 independent layer caches of the 'vggt_stack' workload
-        (budget 16384), which gives the bandwidth kernels launches large enough to be judged
-        against HBM peak;
-    (3) the uncompressed bf16 cache (plain Eq. 1 over every past frame) at 100, 250 and 500 frames
-        of the benchmark workload: per-frame time and cache bytes grow with the stream, which is
-        the growth the compressed cache's flat cost is set against (Sec. 4.3);
-    (4) the matrix-instruction rate and the copy bandwidth this machine sustains."""
-    out = {}
+def aux_vggt_layer(torch, kvx, si, dev, steps):
+    """One layer cache of the second configuration (budget 8192) through kv_step: the latency a model whose
+    layers run one after the other sees per layer."""
     w = si.WORKLOADS["vggt_layer"]
-    n, H, d, L = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens
-    h = kvx.KvHandle(n_heads=H, tokens_per_frame=n, n_special=w.n_special, pool_group=w.pool_group, budget_tokens=L,
-                     k_bits=w.k_bits, k_group=w.k_group, v_bits=w.v_bits, v_group=w.v_group)
-    h.set_option("overlap_update", 0)
-    o = torch.empty((n, H, d), dtype=torch.bfloat16, device=dev)
-    for t in range(12):
-        h.step(*frames[t % len(frames)], o)
-    h.set_timing(1)
-    for t in range(50):
-        h.step(*frames[t % len(frames)], o)
-    torch.cuda.synchronize()
-    ms, cnt = h.read_timing()["attention"]
-    us = ms * 1e3 / cnt
-    out["attention_alone"] = {"us": round(us, 2), "TFLOP/s": round(4.0 * n * (L + n) * d * H / (us * 1e-6) / 1e12, 1)}
-    h.close()
+    run = StackRun(torch, kvx, w, dev, 1, 1, 12, 101)
+    fill = -(-w.budget_tokens // w.tokens_per_frame) + 1
+    run.run(fill + 3)
+    run.h.set_option("timing_every", 8)
+    run.h.set_timing(1)
+    dt = run.timed(steps)
+    ms, cnt = run.h.read_timing()["attention"]
+    run.h.set_timing(0)
+    us = kernel_times(run, min(steps, 50))
+    st = run.h.stats()
+    a_us = ms * 1e3 / max(cnt, 1)
+    out = {"workload": "vggt_layer: 1 layer, budget 8192, INT4/INT4 g64, kv_step per frame",
+           "frames/s": round(steps / dt, 1), "ms_per_step": round(dt * 1e3 / steps, 4),
+           "attention_us": round(a_us, 2), "attention_TFLOP/s": round(attention_flops(w) / (a_us * 1e-6) / 1e12, 1),
+           "attention_frac": round(attention_flops(w) / (a_us * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS, 4),
+           "kernel_us": {k: round(v, 2) for k, v in us.items()},
+           "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "allocated": st["bytes_allocated"]}}
+    run.close()
+    return out
 
-    w = si.WORKLOADS["vggt_stack"]
-    n, H, d, L, NL = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens, w.n_layers
-    h = kvx.KvHandle(n_layers=NL, n_heads=H, tokens_per_frame=n, n_special=w.n_special, pool_group=w.pool_group,
-                     budget_tokens=L, k_bits=w.k_bits, k_group=w.k_group, v_bits=w.v_bits, v_group=w.v_group)
-    outs = [torch.empty((n, H, d), dtype=torch.bfloat16, device=dev) for _ in range(NL)]
-    fill = -(-L // n) + 1
 
-    def step(t):
-        h.step_batched([(0, l, *frames[(t + l) % len(frames)], outs[l]) for l in range(NL)])
-    for t in range(fill + 2):
-        step(t)
-    torch.cuda.synchronize()
-    # throughput as deployed (cache update beside attention), then the kernels one after the other for their own times
-    steps = 10
-    t0 = time.perf_counter()
-    for t in range(steps):
-        step(fill + 2 + t)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    h.set_option("overlap_update", 0)
-    h.set_timing(0x7F)
-    for t in range(steps):
-        step(fill + 2 + steps + t)
-    torch.cuda.synchronize()
-    tm = h.read_timing()
-    kb, vb = w.k_bits, w.v_bits
-    per_layer = {
-        "score": H * L * d * kb / 8 + H * (L // w.k_group) * d * 8 + H * L * 4,
-        "rebuild_k": 2 * (H * L * d * kb / 8 + H * (L // w.k_group) * d * 8) + n * H * d * 2,
-        "rebuild_v": 2 * (H * L * d * vb / 8 + H * L * 8) + n * H * d * 2,
-    }
-    hb = {}
-    for name, nbytes in per_layer.items():
-        ms, cnt = tm[name]
-        us = ms * 1e3 / cnt
-        gbs = NL * nbytes / (us * 1e-6) / 1e9
-        hb[name] = {"us": round(us, 2), "GB/s": round(gbs, 1), "frac": round(gbs / peak_hbm, 4)}
-    # score and key rebuild are bound by vector-instruction issue, not memory: instructions per wave from
-    # rocprofv3 SQ_INSTS_VALU / SQ_WAVES (profiles/update_kernels_vggt_stack_counters.txt, INT4 kernels), one wave
-    # per 64 cached tokens and head (score) or per 16 tokens and head (rebuild), against the chip's issue rate of
-    # one 64-lane instruction per SIMD every 4 cycles: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-instr/s
-    if kb == 4:
-        peak_lane_instr = 256 * 4 * 16 * 2.4e9
-        for name, per_wave, waves in (("score", 413.25, NL * H * (L // 64)), ("rebuild_k", 340.4, NL * H * (L // 16))):
-            rate = per_wave * waves * 64 / (hb[name]["us"] * 1e-6)
-            hb[name]["valu"] = {"bound": "alu", "achieved": round(rate / 1e12, 2), "peak": round(peak_lane_instr / 1e12, 2),
-                                "unit": "T lane-instr/s", "frac": round(rate / peak_lane_instr, 4)}
-    ms, cnt = tm["attention"]
-    us = ms * 1e3 / cnt
-    out["stack24_batched_step"] = {
-        "frames/s (24-layer frames)": round(steps / dt, 2),
-        "kernel_us": {k: round(v[0] * 1e3 / v[1], 2) for k, v in tm.items() if v[1]},
-        "attention_TFLOP/s": round(NL * 4.0 * n * (L + n) * d * H / (us * 1e-6) / 1e12, 1),
-        "hbm_kernels": hb,
-        "kv_bytes_live_per_layer": h.stats()["bytes_live_per_cache"],
-    }
-    h.close()
-
-    w = si.WORKLOADS["vggt_layer"]
-    n, H, d = w.tokens_per_frame, w.n_heads, w.head_dim
-    marks = (100, 250, 500)
-    h = kvx.KvHandle(n_heads=H, tokens_per_frame=n, n_special=w.n_special, pool_group=w.pool_group,
-                     budget_tokens=w.budget_tokens, mode=kvx.KV_UNCOMPRESSED_BF16, max_frames=marks[-1])
-    o = torch.empty((n, H, d), dtype=torch.bfloat16, device=dev)
-    growth = {}
-    t = 0
+def aux_vggt_long(torch, kvx, si, dev, frames_total, unc_marks):
+    """Fourth configuration: 24 layers streamed for frames_total frames with the compressed cache (per-frame time
+    and allocated bytes sampled along the way), against the uncompressed bf16 cache of the same 24 layers at the
+    marks in unc_marks (plain Eq. 1 over every past frame)."""
+    w = si.WORKLOADS["vggt_long"]
+    out = {"workload": f"vggt_long: 24 layers x {frames_total} frames, budget 16384, INT4/INT4 g64"}
+    run = StackRun(torch, kvx, w, dev, 1, w.n_layers, 20, 103)
+    marks = sorted({m for m in (1, 100, 250, 500, 1000) if m <= frames_total} | {frames_total})
+    comp = {}
     for m in marks:
-        while t < m - 5:
-            h.step(*frames[t % len(frames)], o)
-            t += 1
+        span = min(10, m - run.t)
+        run.run(m - span - run.t)
+        dt = run.timed(span)
+        st = run.h.stats()
+        comp[str(m)] = {"ms_per_frame": round(dt * 1e3 / span, 3), "cache_len": st["cache_len_max"],
+                        "bytes_allocated": st["bytes_allocated"], "bytes_live": st["bytes_live_per_cache"] * w.n_layers}
+    out["compressed_by_frames"] = comp
+    frames_c = run.frames
+    run.close()
+    unc = {}
+    last = max(unc_marks)
+    h = kvx.KvHandle(n_layers=w.n_layers, n_heads=w.n_heads, tokens_per_frame=w.tokens_per_frame, n_special=w.n_special,
+                     pool_group=w.pool_group, budget_tokens=w.budget_tokens, mode=kvx.KV_UNCOMPRESSED_BF16, max_frames=last)
+    outs = [torch.empty((w.tokens_per_frame, w.n_heads, w.head_dim), dtype=torch.bfloat16, device=dev) for _ in range(w.n_layers)]
+    t = 0
+
+    def step():
+        nonlocal t
+        r = t % 20
+        h.step_batched([(0, l, frames_c[l][0][r], frames_c[l][1][r], frames_c[l][2][r], outs[l]) for l in range(w.n_layers)])
+        t += 1
+    for m in sorted(unc_marks):
+        while t < m - 3:
+            step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         while t < m:
-            h.step(*frames[t % len(frames)], o)
-            t += 1
+            step()
         torch.cuda.synchronize()
-        growth[str(m)] = {"ms_per_frame": round((time.perf_counter() - t0) * 1e3 / 5, 3),
-                          "cache_bytes": 2 * H * m * n * d * 2}
-    out["uncompressed_bf16_by_frames"] = growth
+        unc[str(m)] = {"ms_per_frame": round((time.perf_counter() - t0) * 1e3 / 3, 2),
+                       "cache_bytes": 2 * w.n_layers * w.n_heads * m * w.tokens_per_frame * w.head_dim * 2,
+                       "bytes_allocated": h.stats()["bytes_allocated"]}
     h.close()
+    out["uncompressed_bf16_by_frames"] = unc
+    return out
 
-    # what this machine sustains: a register-resident bf16 MFMA loop on every CU (~5 ms per launch,
-    # long enough for the clock to settle under the power limit) and a 1 GiB streaming copy
-    out["machine"] = {"mfma_bf16_sustained_TFLOP/s": round(kvx.probe_mfma_bf16(50000, 3), 1),
-                      "hbm_copy_GB/s": round(kvx.probe_copy(1 << 30, 3), 1)}
+
+def aux_vggt_hires(torch, kvx, si, dev, steps):
+    """Fifth configuration: 4 streams x 24 layers, 1374 tokens per frame, budget 24576, INT2 keys g32 / INT4 values."""
+    w = si.WORKLOADS["vggt_hires"]
+    run = StackRun(torch, kvx, w, dev, w.n_streams, w.n_layers, 20, 105)
+    fill = -(-w.budget_tokens // w.tokens_per_frame) + 1
+    run.run(fill + 2)
+    dt = run.timed(steps)
+    us = kernel_times(run, min(steps, 10))
+    st = run.h.stats()
+    launches = 2          # 96 caches = two launches of 48
+    per_launch = w.n_streams * w.n_layers / launches
+    out = {"workload": "vggt_hires: 4 streams x 24 layers in one kv_step_batched, 1374 tokens/frame, budget 24576, INT2 K g32 / INT4 V g64",
+           "frames/s (4-stream x 24-layer frames)": round(steps / dt, 2), "ms_per_step": round(dt * 1e3 / steps, 3),
+           "stream_frames/s": round(w.n_streams * steps / dt, 2),
+           "attention_TFLOP/s": round(per_launch * attention_flops(w) / (us["attention"] * 1e-6) / 1e12, 1),
+           "attention_frac": round(per_launch * attention_flops(w) / (us["attention"] * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS, 4),
+           "kernel_us_per_launch_of_48": {k: round(v, 2) for k, v in us.items()},
+           "hbm_kernels": hbm_report(w, per_launch, us),
+           "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "allocated": st["bytes_allocated"]}}
+    run.close()
     return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=24)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--splits", type=int, default=0, help="override the attention key-range split count")
     ap.add_argument("--no-overlap", action="store_true", help="run the cache update after attention instead of beside it")
-    ap.add_argument("--no-aux", action="store_true", help="skip the auxiliary measurements (standalone attention, 24-layer batched step)")
+    ap.add_argument("--no-aux", action="store_true", help="skip the other configurations (one layer, long stream, high-resolution multi-stream)")
+    ap.add_argument("--long-frames", type=int, default=1000, help="frames of the long-stream run in aux")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 1 GiB device-to-device copies (copy_probe_kernel), the known-size reference for HBM byte counters")
     args = ap.parse_args()
@@ -187,127 +298,84 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     import paper_2601_01204_amd as kvx
     import synth_inputs as si
 
-    w = si.WORKLOADS["vggt_layer"]
     dev = torch.device("cuda:0")
-    n, H, d, L = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens
-    h = kvx.KvHandle(n_heads=H, tokens_per_frame=n, n_special=w.n_special, pool_group=w.pool_group, budget_tokens=L,
-                     k_bits=w.k_bits, k_group=w.k_group, v_bits=w.v_bits, v_group=w.v_group, in_dtype=kvx.KV_BF16,
-                     out_dtype=kvx.KV_BF16)
-    if args.splits:
-        h.set_option("attention_splits", args.splits)
-    if args.no_overlap:
-        h.set_option("overlap_update", 0)
-
     if args.copy_calibration:
         kvx.probe_copy(1 << 30, 3)
 
-    # a ring of distinct frames, resident in HBM
-    ring = w.frames
-    sigma = si.key_channel_scales(w)
-    frames = []
-    for t in range(ring):
-        q, k, v = si.frame_qkv(w, t, sigma=sigma)
-        frames.append(tuple(torch.from_numpy(a).to(dev).to(torch.bfloat16) for a in (q, k, v)))
-    out = torch.empty((n, H, d), dtype=torch.bfloat16, device=dev)
-    stream = torch.cuda.current_stream().cuda_stream
-
-    fill = -(-L // n) + 1                       # frames until the cache is full and pruning every step
+    w = si.WORKLOADS["vggt_stack"]
+    n, H, d, L, NL = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens, w.n_layers
+    run = StackRun(torch, kvx, w, dev, 1, NL, 20, 102)
+    if args.splits:
+        run.h.set_option("attention_splits", args.splits)
+    if args.no_overlap:
+        run.h.set_option("overlap_update", 0)
+    fill = -(-L // n) + 1                       # frames until every cache is full and prunes every step
     warm = max(args.warmup, fill)
-    t_idx = 0
-    for _ in range(warm):
-        q, k, v = frames[t_idx % ring]
-        h.step(q, k, v, out, hip_stream=stream)
-        t_idx += 1
+    run.run(warm)
     torch.cuda.synchronize()
-    assert h.stats()["cache_len_max"] == L
+    assert run.h.stats()["cache_len_min"] == L
 
-    # HIP events around the attention kernel, on its stream, on every 8th step of the timed region: an event
-    # pair costs the stream about 6 us, which would otherwise come out of every step of the headline figure
-    h.set_option("timing_every", 8)
-    h.set_timing(1 << 0)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        q, k, v = frames[t_idx % ring]
-        h.step(q, k, v, out, hip_stream=stream)
-        t_idx += 1
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    attn_ms, attn_cnt = h.read_timing()["attention"]
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    assert bool(torch.isfinite(out.float()).all())
+    # HIP events around the attention kernel on its own stream, inside the timed region (a pair costs the stream
+    # a few microseconds of a 3 ms step)
+    run.h.set_option("timing_every", 1)
+    run.h.set_timing(1 << 0)
+    dt = run.timed(args.steps)
+    attn_ms, attn_cnt = run.h.read_timing()["attention"]
+    run.h.set_timing(0)
+    assert all(bool(torch.isfinite(o.float()).all()) for o in run.outs)
+    us = kernel_times(run, min(args.steps, 20))
+    st = run.h.stats()
 
-    # per-kernel durations of the whole step (separate pass: the extra events perturb the stream a little)
-    h.set_option("timing_every", 1)
-    h.set_timing(0x7F)
-    for _ in range(min(args.steps, 50)):
-        q, k, v = frames[t_idx % ring]
-        h.step(q, k, v, out, hip_stream=stream)
-        t_idx += 1
-    torch.cuda.synchronize()
-    per_kernel = h.read_timing()
-    h.set_timing(0)
-    st = h.stats()
-
-    T = L + n
-    flops = 4.0 * n * T * d * H
+    flops = NL * attention_flops(w)
     attn_s = attn_ms * 1e-3 / max(attn_cnt, 1)
     achieved = flops / attn_s / 1e12
-    kb, vb = w.k_bits, w.v_bits
-    mid = L - n
-    alg_bytes = {
-        # middle key codes + their (s, z) + the D[h, j] written
-        "score": H * L * d * kb / 8 + H * (L // w.k_group) * d * 8 + H * L * 4,
-        # survivors' key codes + (s, z) read, new frame read, next cache written
-        "rebuild_k": 2 * (H * L * d * kb / 8 + H * (L // w.k_group) * d * 8) + n * H * d * 2,
-        "rebuild_v": 2 * (H * L * d * vb / 8 + H * L * 8) + n * H * d * 2,
-        "select": H * mid * 4 + 6 * mid * 4 + L * 4,
-    }
-    hbm = {}
-    for name, nbytes in alg_bytes.items():
-        ms, cnt = per_kernel[name]
-        if cnt:
-            us = ms * 1e3 / cnt
-            hbm[name] = {"us": round(us, 2), "GB/s": round(nbytes / (us * 1e-6) / 1e9, 1), "frac": round(nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}
-    kernels_us = {k: round(v[0] * 1e3 / v[1], 2) for k, v in per_kernel.items() if v[1]}
-
     res = {
         "metric": "frames/s of compressed-KV causal attention step",
-        "value": round(args.steps / (t1 - t0), 2),
+        "value": round(args.steps / dt, 2),
         "unit": "frames/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": warm,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": round(dt * 1e3 / args.steps, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "vggt_layer: 1 layer, 16 heads x 64, 1041 tokens/frame, budget 8192, INT4 K per-channel g64 / INT4 V per-token g64, steady state",
-                   "keys_per_step": T, "attention_splits": args.splits or "auto"},
+        "config": {"workload": "vggt_stack: 24 layer caches per frame in one kv_step_batched, 16 heads x 64, 1041 tokens/frame, budget "
+                               "16384 tokens/layer, INT4 K per-channel g64 / INT4 V per-token g64, fp32 scale + int32 zero-point, steady state",
+                   "keys_per_step": L + n, "layers": NL, "attention_splits": args.splits or "auto"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": ATTENTION_TRAFFIC_BYTES,
+                     "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": attention_traffic("vggt_stack", "f32"),
                      "kernel": "attn_kernel", "flops_per_launch": flops, "avg_launch_us": round(attn_s * 1e6, 2)},
-        "hbm_kernels": hbm,
-        "kernel_us": kernels_us,
-        "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "allocated": st["bytes_allocated"],
-                     "bf16_uncompressed_equivalent": 2 * H * L * d * 2},
+        "hbm_kernels": hbm_report(w, NL, us),
+        "kernel_us": {k: round(v, 2) for k, v in us.items()},
+        "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "live_per_frame_step": st["bytes_live_per_cache"] * NL,
+                     "allocated": st["bytes_allocated"], "allocated_per_cache": st["bytes_allocated"] // NL,
+                     "bf16_uncompressed_equivalent_per_cache": 2 * H * L * d * 2,
+                     "allocated_over_bf16_equivalent": round(st["bytes_allocated"] / NL / (2 * H * L * d * 2), 3)},
     }
-    h.close()
-
-    if not args.no_aux:
-        res["aux"] = aux_measurements(torch, kvx, si, dev, frames, PEAK_HBM_GBS)
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = oracle_baseline(w)
+        res["cpu_baseline"] = oracle_baseline(torch, run, fill + 3, 3)
     else:
         res["cpu_baseline"] = None
+    run.close()
+
+    if not args.no_aux:
+        aux = {}
+        aux["vggt_layer"] = aux_vggt_layer(torch, kvx, si, dev, max(args.steps, 50))
+        aux["vggt_long"] = aux_vggt_long(torch, kvx, si, dev, args.long_frames, (100, 250, 500))
+        aux["vggt_hires"] = aux_vggt_hires(torch, kvx, si, dev, min(args.steps, 20))
+        # what this machine sustains: a register-resident bf16 MFMA loop on every CU (~5 ms per launch,
+        # long enough for the clock to settle under the power limit) and a 1 GiB streaming copy
+        aux["machine"] = {"mfma_bf16_sustained_TFLOP/s": round(kvx.probe_mfma_bf16(50000, 3), 1),
+                          "hbm_copy_GB/s": round(kvx.probe_copy(1 << 30, 3), 1)}
+        res["aux"] = aux
     print(json.dumps(res))
 
 

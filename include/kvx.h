@@ -17,7 +17,10 @@
  * "host" pointers are ordinary host memory.  The library owns the cache, the
  * caller owns q/k/v/out.  No call throws or aborts; every call returns a
  * kv_status (0 = ok, negative = error) and kv_last_error() gives the text.
- * A handle is not thread-safe.  Steps on one cache must be stream-ordered.
+ * A handle is not thread-safe.  All kv_step / kv_step_batched calls on one handle must be
+ * stream-ordered with each other, whatever caches they name: the partial-result buffers of
+ * the attention kernel and the library's second stream belong to the handle, not to a cache.
+ * Callers that want two caches to progress on two HIP streams at once use two handles.
  */
 #ifndef KVX_H
 #define KVX_H
@@ -137,19 +140,34 @@ int kv_init(const kv_config* cfg, kv_handle** out);
 int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v,
             int64_t tok_stride, int64_t head_stride, void* out, void* hip_stream);
 
-/* The same for n_items distinct caches in one set of launches (independent streams, or
- * independent layers of a synthetic stack).  items: host array. */
+/* The same for n_items distinct caches in one set of launches.  Sec. 3.1 gives every layer
+ * its own cache (the layer superscript of Eq. 1) and Sec. 3.2 / 3.3 prune and quantise each
+ * layer's cache from that layer's own queries and keys, so the caches of one call are
+ * independent: streams of different videos, or the layers of a synthetic stack whose inputs
+ * do not depend on each other.  items: host array of n_items records (a cache may appear
+ * once); strides as in kv_step, shared by all items.  More than 48 items are issued as
+ * several launch sets.  KV_E_INVAL / KV_E_RANGE before anything is launched. */
 int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride,
                     int64_t head_stride, void* hip_stream);
 
-/* Counters and footprint.  stats: host.  Synchronises the device. */
+/* Counters and footprint.  Sec. 3.2 bounds every cache by L_max (cache_len_max never
+ * exceeds budget_tokens; tokens_dropped_total counts what the top-k of Sec. 3.2 removed),
+ * and Sec. 3.3's codes and (s, z) are what bytes_live_per_cache adds up, the figure behind
+ * the paper's memory comparison (Sec. 4, efficiency analysis).  stats: host, overwritten.
+ * Synchronises the device. */
 int kv_stats(kv_handle* h, kv_stats_t* stats);
 
-/* Copy one cache to host buffers with codes unpacked (parity checks, checkpoints).
- * Synchronises the device.  bufs: host struct of host pointers. */
+/* Copy one cache to host buffers: the stored state of Sec. 3.3 (codes of Eq. 7, scales and
+ * zero-points of Eq. 8, keys grouped per channel and values per token as in Eq. 9), the token
+ * ids in cache order, and the last step's keep set and importance scores (Sec. 3.2, Eq. 6).
+ * Codes are unpacked to one per byte.  Used by parity checks and as a checkpoint.
+ * Synchronises the device.  bufs: host struct of host pointers, capacity_tokens set by the
+ * caller; KV_E_RANGE if it is below the cache length. */
 int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* bufs);
 
-/* Forget the contents of one cache (stream, layer), or of all with stream = layer = -1. */
+/* Forget the contents of one cache (stream, layer), or of all with stream = layer = -1: the
+ * next frame is again the first frame of its stream, the one Sec. 3.2 never prunes.  Host
+ * bookkeeping only; the caller orders it after the steps already enqueued on that cache. */
 int kv_reset(kv_handle* h, int32_t stream, int32_t layer);
 
 /* Load a cache from host buffers laid out as kv_export writes them (the checkpoint of a
