@@ -140,6 +140,23 @@ int kv_init(const kv_config* cfg, kv_handle** out);
 int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v,
             int64_t tok_stride, int64_t head_stride, void* out, void* hip_stream);
 
+/* kv_step for callers that cannot allocate device memory or let a library do so around the call:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same results as kv_step (same kernels, same cache update), but the attention
+ * kernel's key-range splits leave their partial results in a static device array of
+ * KV_STATIC_SCRATCH_BYTES bytes that is part of the library's code object (each GPU the library
+ * runs on holds its own copy until the process ends) instead of in the buffers kv_init
+ * allocated, and the call makes no hipMalloc / hipFree / event-creation call of its own (launch
+ * timing of kv_set_timing is not recorded for it).  Fewer splits are used when the array holds
+ * fewer than kv_step would choose; KV_E_RANGE, with nothing launched, when the partial results
+ * of two splits, 2 * n_heads * (tokens_per_frame rounded up to the query tiling) * 264 bytes,
+ * exceed the array.  Every call on a GPU shares that GPU's array: nothing in it has to start at
+ * zero (each call overwrites what it reads), but two calls that overlap in time on one GPU,
+ * from any handles or streams, race on it; order them on one stream. */
+#define KV_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+int kv_step_static(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v,
+                   int64_t tok_stride, int64_t head_stride, void* out, void* hip_stream);
+
 /* The same for n_items distinct caches in one set of launches.  Sec. 3.1 gives every layer
  * its own cache (the layer superscript of Eq. 1) and Sec. 3.2 / 3.3 prune and quantise each
  * layer's cache from that layer's own queries and keys, so the caches of one call are

@@ -67,6 +67,7 @@ def load_library():
     P = C.c_void_p
     lib.kv_init.argtypes = [C.POINTER(KvConfig), C.POINTER(P)]
     lib.kv_step.argtypes = [P, C.c_int32, C.c_int32, P, P, P, C.c_int64, C.c_int64, P, P]
+    lib.kv_step_static.argtypes = [P, C.c_int32, C.c_int32, P, P, P, C.c_int64, C.c_int64, P, P]
     lib.kv_step_batched.argtypes = [P, C.c_int32, C.POINTER(KvStepItem), C.c_int64, C.c_int64, P]
     lib.kv_stats.argtypes = [P, C.POINTER(KvStats)]
     lib.kv_export.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(KvExport)]
@@ -81,7 +82,7 @@ def load_library():
     lib.kv_set_option.argtypes = [P, C.c_char_p, C.c_int64]
     lib.kv_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, P, C.POINTER(C.c_double)]
     lib.kv_probe_copy.argtypes = [C.c_int64, C.c_int32, P, C.POINTER(C.c_double)]
-    for name in ("kv_init", "kv_step", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_timing",
+    for name in ("kv_init", "kv_step", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_timing",
                  "kv_read_timing", "kv_set_option", "kv_probe_mfma_bf16", "kv_probe_copy", "kv_import"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -141,6 +142,15 @@ class KvHandle:
         assert self._strides(out) == (ts, hs)
         self._check(self.lib.kv_step(self._h, stream, layer, q.data_ptr(), k.data_ptr(), v.data_ptr(), ts, hs,
                                      out.data_ptr(), hip_stream))
+
+    def step_static(self, q, k, v, out, stream: int = 0, layer: int = 0, hip_stream: int = 0):
+        """kv_step_static: kv_step with the attention partials in the library's static device array."""
+        ts, hs = self._strides(q)
+        for t in (k, v):
+            assert self._strides(t) == (ts, hs) and t.dtype == q.dtype
+        assert self._strides(out) == (ts, hs)
+        self._check(self.lib.kv_step_static(self._h, stream, layer, q.data_ptr(), k.data_ptr(), v.data_ptr(), ts, hs,
+                                            out.data_ptr(), hip_stream))
 
     def step_batched(self, items, hip_stream: int = 0):
         """items: list of (stream, layer, q, k, v, out)."""

@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -35,6 +36,32 @@ struct TimedLaunch {
 
 thread_local std::string g_init_error;
 
+// Partial results of the attention kernel's key-range splits for kv_step_static, the entry point that
+// must not allocate.  Every GPU the library runs on holds its own copy of this array until the process
+// ends.  In host code the name is only a stand-in for the symbol: the address a kernel can use is taken
+// once per device with hipGetSymbolAddress (static_scratch_address below) and passed on as a pointer.
+constexpr size_t kStaticScratchBytes = (size_t)KV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices] = {};
+std::mutex g_static_scratch_lock;
+
+// The address of `scratch` on `device`, which must be the current device.
+hipError_t static_scratch_address(int device, void** out) {
+  *out = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(g_static_scratch_lock);
+  if (!g_static_scratch[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_static_scratch[device] = p;
+  }
+  *out = g_static_scratch[device];
+  return hipSuccess;
+}
+
 int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
@@ -43,8 +70,11 @@ struct kv_handle {
   kv_config cfg{};
   Geometry geo{};
   std::vector<CacheState> caches;
+  std::vector<int64_t> seen_in_call;   // per cache: the step call that last named it (duplicate check without a per-call allocation)
+  int64_t call_id = 0;
   uint8_t* arena = nullptr;
-  uint8_t* scratch = nullptr;
+  uint8_t* work = nullptr;             // per-cache working memory (pooled query, dots, scores, keep list, counters)
+  void* static_scratch = nullptr;      // this device's address of the file-scope `scratch` array (kv_step_static)
   float* part_o = nullptr;
   float* part_ml = nullptr;
   int64_t bytes_arena = 0, bytes_scratch = 0, bytes_part = 0;
@@ -253,9 +283,19 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   }
   h->n_cus = cus;
   h->target_wgs = std::max(1, cus * 3 / 4);
+  {
+    const hipError_t e = static_scratch_address(h->device, &h->static_scratch);
+    if (e != hipSuccess) {
+      rc = fail(nullptr, KV_E_HIP, "kv_init: address of the static scratch array: %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+      delete h;
+      return rc;
+    }
+  }
 
   const int64_t n_caches = (int64_t)c.n_streams * c.n_layers;
   h->caches.assign((size_t)n_caches, CacheState());
+  h->seen_in_call.assign((size_t)n_caches, 0);
   h->slots_cap = 0;
   for (int items = 1; items <= std::min<int64_t>(kMaxItems, n_caches); ++items) {
     // the most splits pick_splits can choose for this many items when it aims at every compute unit
@@ -271,7 +311,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   h->bytes_part = part_o_bytes + part_ml_bytes;
 
   hipError_t e1 = hipMalloc((void**)&h->arena, (size_t)h->bytes_arena);
-  hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&h->scratch, (size_t)h->bytes_scratch) : e1;
+  hipError_t e2 = e1 == hipSuccess ? hipMalloc((void**)&h->work, (size_t)h->bytes_scratch) : e1;
   hipError_t e3 = e2 == hipSuccess ? hipMalloc((void**)&h->part_o, (size_t)part_o_bytes) : e2;
   hipError_t e4 = e3 == hipSuccess ? hipMalloc((void**)&h->part_ml, (size_t)part_ml_bytes) : e3;
   if (e4 != hipSuccess) {
@@ -281,7 +321,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
     kv_destroy(h);
     return rc;
   }
-  if (hipMemset(h->arena, 0, (size_t)h->bytes_arena) != hipSuccess || hipMemset(h->scratch, 0, (size_t)h->bytes_scratch) != hipSuccess ||
+  if (hipMemset(h->arena, 0, (size_t)h->bytes_arena) != hipSuccess || hipMemset(h->work, 0, (size_t)h->bytes_scratch) != hipSuccess ||
       hipDeviceSynchronize() != hipSuccess) {
     rc = fail(nullptr, KV_E_HIP, "kv_init: clearing the arena failed: %s", hipGetErrorString(hipGetLastError()));
     kv_destroy(h);
@@ -294,15 +334,22 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
     return rc;
   }
   g.arena = h->arena;
-  g.scratch = h->scratch;
+  g.scratch = h->work;
   g.part_o = h->part_o;
   g.part_ml = h->part_ml;
   *out = h;
   return KV_OK;
 }
 
-int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride, int64_t head_stride, void* hip_stream) {
-  if (!h) return KV_E_INVAL;
+}  // extern "C"
+
+namespace {
+
+// One set of launches per group of up to kMaxItems caches.  part_o / part_ml: where the attention
+// kernel's key-range splits leave their partial results, room for slots_cap (cache, split) pairs.
+// with_timing = false: no event is created or recorded by this call.
+int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride, int64_t head_stride, void* hip_stream,
+              float* part_o, float* part_ml, int32_t slots_cap, bool with_timing) {
   if (n_items < 1 || !items) return fail(h, KV_E_INVAL, "kv_step: no items");
   const kv_config& c = h->cfg;
   const Geometry& g0 = h->geo;
@@ -311,7 +358,7 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
   const int64_t oelt = g0.out_f32 ? 4 : 2;
   if ((tok_stride * elt) % 16 || (head_stride * elt) % 16 || (tok_stride * oelt) % 16 || (head_stride * oelt) % 16)
     return fail(h, KV_E_INVAL, "kv_step: strides must keep rows 16-byte aligned");
-  std::vector<char> seen(h->caches.size(), 0);
+  const int64_t call = ++h->call_id;
   for (int i = 0; i < n_items; ++i) {
     const kv_step_item& it = items[i];
     if (it.stream < 0 || it.stream >= c.n_streams || it.layer < 0 || it.layer >= c.n_layers)
@@ -320,13 +367,13 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
     if (((uintptr_t)it.q | (uintptr_t)it.k | (uintptr_t)it.v | (uintptr_t)it.out) & 15)
       return fail(h, KV_E_INVAL, "kv_step: item %d: pointers must be 16-byte aligned", i);
     const size_t ci = (size_t)it.stream * c.n_layers + it.layer;
-    if (seen[ci]) return fail(h, KV_E_INVAL, "kv_step: cache (stream %d, layer %d) appears twice in one batch", it.stream, it.layer);
-    seen[ci] = 1;
+    if (h->seen_in_call[ci] == call) return fail(h, KV_E_INVAL, "kv_step: cache (stream %d, layer %d) appears twice in one batch", it.stream, it.layer);
+    h->seen_in_call[ci] = call;
     if (g0.uncompressed && h->caches[ci].frames >= c.max_frames)
       return fail(h, KV_E_STATE, "kv_step: cache (stream %d, layer %d) already holds max_frames frames", it.stream, it.layer);
   }
   hipStream_t st = (hipStream_t)hip_stream;
-  h->timing_now = h->timing_mask != 0 && (h->step_calls % h->timing_every) == 0;
+  h->timing_now = with_timing && h->timing_mask != 0 && (h->step_calls % h->timing_every) == 0;
   h->step_calls += 1;
 
   for (int base = 0; base < n_items; base += kMaxItems) {
@@ -360,8 +407,10 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
       const int tiles = (cs.t_c + kTileK - 1) / kTileK + (g0.n + kTileK - 1) / kTileK;
       min_tiles = std::min(min_tiles, tiles);
     }
+    b.g.part_o = part_o;
+    b.g.part_ml = part_ml;
     b.g.n_splits = pick_splits(h, cnt, min_tiles);
-    if (cnt * b.g.n_splits > h->slots_cap) b.g.n_splits = std::max(1, h->slots_cap / cnt);
+    if (cnt * b.g.n_splits > slots_cap) b.g.n_splits = std::max(1, slots_cap / cnt);
 
     hipStream_t sb = st;          // stream of the cache-update chain
     if (h->overlap && h->side && !g0.uncompressed) {
@@ -427,6 +476,38 @@ int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, in
   return KV_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride, int64_t head_stride, void* hip_stream) {
+  if (!h) return KV_E_INVAL;
+  return step_impl(h, n_items, items, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->slots_cap, true);
+}
+
+int kv_step_static(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v, int64_t tok_stride,
+                   int64_t head_stride, void* out, void* hip_stream) {
+  if (!h) return KV_E_INVAL;
+  const Geometry& g = h->geo;
+  // one (cache, split) slot: [H][n_pad][64] fp32 partial outputs + [H][n_pad][2] fp32 (max, sum), the two parts 256-byte aligned
+  const int64_t slot_o = (int64_t)g.H * g.n_pad * kHeadDim * 4, slot_ml = (int64_t)g.H * g.n_pad * 2 * 4;
+  const int64_t slots = std::min<int64_t>((int64_t)kStaticScratchBytes / (slot_o + slot_ml + 512), kMaxSplits);
+  if (slots < 2)
+    return fail(h, KV_E_RANGE, "kv_step_static: n_heads x tokens_per_frame = %d x %d needs %lld bytes for the partial results of two key-range "
+                "splits, above the static scratch of %lld bytes", g.H, g.n, (long long)(2 * (slot_o + slot_ml)), (long long)kStaticScratchBytes);
+  if (!h->static_scratch) return fail(h, KV_E_STATE, "kv_step_static: the static scratch array has no address on this device");
+  float* part_o = reinterpret_cast<float*>(h->static_scratch);
+  float* part_ml = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(h->static_scratch) + align_up(slots * slot_o, 256));
+  kv_step_item it;
+  it.stream = stream;
+  it.layer = layer;
+  it.q = q;
+  it.k = k;
+  it.v = v;
+  it.out = out;
+  return step_impl(h, 1, &it, tok_stride, head_stride, hip_stream, part_o, part_ml, (int32_t)slots, false);
+}
+
 int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v, int64_t tok_stride,
             int64_t head_stride, void* out, void* hip_stream) {
   kv_step_item it;
@@ -464,7 +545,7 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
     mx = std::max(mx, cs.t_c);
     if (!g.uncompressed) {
       int32_t sel[8];
-      if (hipMemcpy(sel, h->scratch + (int64_t)i * g.sl.bytes + g.sl.sel, sizeof sel, hipMemcpyDeviceToHost) != hipSuccess)
+      if (hipMemcpy(sel, h->work + (int64_t)i * g.sl.bytes + g.sl.sel, sizeof sel, hipMemcpyDeviceToHost) != hipSuccess)
         return fail(h, KV_E_HIP, "kv_stats: %s", hipGetErrorString(hipGetLastError()));
       s->k_groups_rebuilt_total += sel[2];
       s->zp_range_warnings += sel[5];
@@ -501,7 +582,7 @@ int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* x) {
   x->last_keep_len = cs.last_pruned ? g.budget : 0;
   x->last_scores_len = cs.last_scores_len;
   const uint8_t* half = h->arena + (int64_t)ci * g.lay.cache_bytes + (int64_t)cs.cur * g.lay.half_bytes;
-  const uint8_t* sc = h->scratch + (int64_t)ci * g.sl.bytes;
+  const uint8_t* sc = h->work + (int64_t)ci * g.sl.bytes;
   const int H = g.H;
   const int G = (T + g.k_group - 1) / g.k_group;
   const int ngv = kHeadDim / g.v_group;
@@ -627,7 +708,7 @@ void kv_destroy(kv_handle* h) {
   if (h->ev_fork) hipEventDestroy(h->ev_fork);
   if (h->ev_join) hipEventDestroy(h->ev_join);
   if (h->arena) hipFree(h->arena);
-  if (h->scratch) hipFree(h->scratch);
+  if (h->work) hipFree(h->work);
   if (h->part_o) hipFree(h->part_o);
   if (h->part_ml) hipFree(h->part_ml);
   delete h;
