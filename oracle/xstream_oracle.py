@@ -28,7 +28,9 @@ notes): attention runs before pruning; the current frame enters its own
 attention at input precision; a short last patch group is averaged over its
 own size; ties in top-k keep the lower cache position and survivors stay in
 ascending position order; rounding is to nearest-even; the zero-point is not
-clamped; a quantisation group is re-quantised only when its ordered member
+clamped (with 16-bit metadata, the meta16 switch, scales are rounded up to their
+storage format before anything is computed from them and zero-points are kept
+to 12 bits); a quantisation group is re-quantised only when its ordered member
 list changed (so value groups, one token each, are quantised once); a short
 trailing key group is quantised over the tokens present; a constant group gets
 scale |min| (1 if min is 0).
@@ -63,6 +65,7 @@ class OracleConfig:
     softmax_scale: float = 0.0       # 0 -> 1/sqrt(head_dim)
     quant: bool = True               # False: keep fp32 K/V (pruning only)
     requant_v: bool = False          # True: re-quantise V every step (literal reading; diagnostic)
+    meta16: bool = False             # True: 16-bit scales and zero-points (see quant_params_meta16_k / _v)
 
 
 # --------------------------------------------------------------------------
@@ -87,6 +90,58 @@ def quant_params(mn: np.ndarray, mx: np.ndarray, bits: int):
     return s, z
 
 
+# 16-bit metadata (the storage the paper's quantiser, KIVI with INT4 and group 64 in its
+# experimental setup, keeps its scales in).  A scale that is rounded for storage has to be
+# rounded *up*, and before the zero-point and the codes are computed from it, or the group's
+# maximum would leave the code range and the s/2 error bound of Eq. 7-8 would break.
+META16_S_MIN = F32(2.0 ** -14)       # smallest normal half
+META16_S_MAX = F32(2048.0)
+META16_Z_MIN, META16_Z_MAX = -1024, 1023
+
+
+def round_up_sig_bits(x: np.ndarray, bits: int) -> np.ndarray:
+    """Smallest fp32 value >= x (x > 0, finite) that has at most `bits` significant bits."""
+    u = np.ascontiguousarray(x, dtype=F32).view(np.uint32).astype(np.uint64)
+    mask = np.uint64((1 << (24 - bits)) - 1)
+    up = (u | mask) + np.uint64(1)
+    return np.where((u & mask) != 0, up, u).astype(np.uint32).view(F32).reshape(np.shape(x))
+
+
+def logit_scale_log2(softmax_scale: float) -> np.float32:
+    """softmax scale times log2(e) as one fp32 product: the factor that takes q . k to the
+    base-2 logit of Eq. 1's softmax."""
+    return F32(F32(softmax_scale) * F32(1.4426950408889634))
+
+
+def quant_params_meta16_k(mn: np.ndarray, mx: np.ndarray, bits: int, c_log2: np.float32):
+    """Eq. 8 for a key group with 16-bit metadata.
+
+    What is stored is the scale in the logit domain, a = s * c_log2 (the step of one code in
+    the base-2 logit per unit of query), rounded up to 7 significant bits and kept inside the
+    half range [2^-14, 2048]: with 7 bits, a * (code - z) is exact in an 11-bit significand for
+    |code - z| <= 16, so the de-quantised key enters Eq. 1 without a further rounding.  The
+    scale that Eq. 7 / Eq. 10 use is s = a / c_log2 (fp32 divide).  The zero-point is kept in
+    [-1024, 1023] (12 bits, exact beside a code in a half).  Returns (a, s, z).
+    """
+    mn = np.asarray(mn, dtype=F32)
+    s_raw, _ = quant_params(mn, mx, bits)
+    a_raw = (s_raw * c_log2).astype(F32)
+    a = np.clip(round_up_sig_bits(a_raw, 7), META16_S_MIN, META16_S_MAX).astype(F32)
+    s = (a / c_log2).astype(F32)
+    z = np.clip(np.rint((-mn) / s), META16_Z_MIN, META16_Z_MAX).astype(np.int32)
+    return a, s, z
+
+
+def quant_params_meta16_v(mn: np.ndarray, mx: np.ndarray, bits: int):
+    """Eq. 8 for a value group with 16-bit metadata: s rounded up to a half (11 significant
+    bits) inside [2^-14, 2048], z in [-1024, 1023].  Returns (s, z)."""
+    mn = np.asarray(mn, dtype=F32)
+    s_raw, _ = quant_params(mn, mx, bits)
+    s = np.clip(round_up_sig_bits(s_raw, 11), META16_S_MIN, META16_S_MAX).astype(F32)
+    z = np.clip(np.rint((-mn) / s), META16_Z_MIN, META16_Z_MAX).astype(np.int32)
+    return s, z
+
+
 def quant_codes(x: np.ndarray, s: np.ndarray, z: np.ndarray, bits: int) -> np.ndarray:
     """Eq. 7: clamp(round(x / s) + z, 0, 2^b - 1); fp32 divide, ties to even."""
     x = np.asarray(x, dtype=F32)
@@ -100,20 +155,24 @@ def dequant(codes: np.ndarray, s: np.ndarray, z: np.ndarray) -> np.ndarray:
     return (s.astype(F32) * diff).astype(F32)
 
 
-def quantize_k_group(xg: np.ndarray, bits: int):
+def quantize_k_group(xg: np.ndarray, bits: int, meta16_c_log2=None):
     """Per-channel key quantisation (Eq. 9) of one group.
 
     xg: fp32 [H, m, d], m <= k_group tokens.  One (s, z) per (head, channel),
-    taken over the m tokens.
+    taken over the m tokens.  meta16_c_log2: None for fp32 metadata, else the
+    logit factor of quant_params_meta16_k.
     """
     mn = xg.min(axis=1)
     mx = xg.max(axis=1)
-    s, z = quant_params(mn, mx, bits)
+    if meta16_c_log2 is None:
+        s, z = quant_params(mn, mx, bits)
+    else:
+        _, s, z = quant_params_meta16_k(mn, mx, bits, meta16_c_log2)
     codes = quant_codes(xg, s[:, None, :], z[:, None, :], bits)
     return codes, s, z
 
 
-def quantize_v_tokens(xv: np.ndarray, bits: int, v_group: int):
+def quantize_v_tokens(xv: np.ndarray, bits: int, v_group: int, meta16: bool = False):
     """Per-token value quantisation (Eq. 9).
 
     xv: fp32 [H, m, d].  One (s, z) per (head, token, group of v_group channels).
@@ -124,7 +183,7 @@ def quantize_v_tokens(xv: np.ndarray, bits: int, v_group: int):
     xr = xv.reshape(H, m, ng, v_group)
     mn = xr.min(axis=3)
     mx = xr.max(axis=3)
-    s, z = quant_params(mn, mx, bits)
+    s, z = quant_params_meta16_v(mn, mx, bits) if meta16 else quant_params(mn, mx, bits)
     codes = quant_codes(xr, s[..., None], z[..., None], bits).reshape(H, m, d)
     return codes, s, z
 
@@ -360,10 +419,10 @@ class OracleCache:
 
         # Values: quantised once when their frame is appended, then carried (their
         # one-token groups never change membership).
-        vc_new, vs_new, vz_new = quantize_v_tokens(v_new, c.v_bits, c.v_group)
+        vc_new, vs_new, vz_new = quantize_v_tokens(v_new, c.v_bits, c.v_group, c.meta16)
         if c.requant_v:
             v_fin = v_all[:, keep, :]
-            Vc, Vs, Vz = quantize_v_tokens(v_fin, c.v_bits, c.v_group)
+            Vc, Vs, Vz = quantize_v_tokens(v_fin, c.v_bits, c.v_group, c.meta16)
         else:
             Vc = np.concatenate([self.Vc, vc_new], axis=1)[:, keep, :]
             Vs = np.concatenate([self.Vs, vs_new], axis=1)[:, keep, :]
@@ -386,7 +445,7 @@ class OracleCache:
                 Ks[:, m, :] = self.Ks[:, m, :]
                 Kz[:, m, :] = self.Kz[:, m, :]
             else:
-                codes, s, z = quantize_k_group(k_fin[:, a:b, :], c.k_bits)
+                codes, s, z = quantize_k_group(k_fin[:, a:b, :], c.k_bits, logit_scale_log2(scale) if c.meta16 else None)
                 Kc[:, a:b, :] = codes
                 Ks[:, m, :] = s
                 Kz[:, m, :] = z
