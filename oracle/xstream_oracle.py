@@ -120,14 +120,17 @@ def quant_params_meta16_k(mn: np.ndarray, mx: np.ndarray, bits: int, c_log2: np.
     the base-2 logit per unit of query), rounded up to 7 significant bits and kept inside the
     half range [2^-14, 2048]: with 7 bits, a * (code - z) is exact in an 11-bit significand for
     |code - z| <= 16, so the de-quantised key enters Eq. 1 without a further rounding.  The
-    scale that Eq. 7 / Eq. 10 use is s = a / c_log2 (fp32 divide).  The zero-point is kept in
-    [-1024, 1023] (12 bits, exact beside a code in a half).  Returns (a, s, z).
+    scale that Eq. 7 / Eq. 10 use is s = a * (1 / c_log2), the reciprocal rounded to fp32 once
+    and one fp32 multiply per scale (every consumer of a stored scale re-derives s, so it is a
+    multiply rather than a divide).  The zero-point is kept in [-1024, 1023] (12 bits, exact
+    beside a code in a half).  Returns (a, s, z).
     """
     mn = np.asarray(mn, dtype=F32)
     s_raw, _ = quant_params(mn, mx, bits)
     a_raw = (s_raw * c_log2).astype(F32)
     a = np.clip(round_up_sig_bits(a_raw, 7), META16_S_MIN, META16_S_MAX).astype(F32)
-    s = (a / c_log2).astype(F32)
+    inv_c = F32(F32(1.0) / c_log2)
+    s = (a * inv_c).astype(F32)
     z = np.clip(np.rint((-mn) / s), META16_Z_MIN, META16_Z_MAX).astype(np.int32)
     return a, s, z
 

@@ -142,12 +142,13 @@ def test_saturation_of_scale_and_zero_point():
 
 def test_scale_follows_the_softmax_scale():
     """The stored key scale is a logit-domain quantity: with another softmax scale the same group
-    gets another grid point, and s = a / c always reproduces from what is stored."""
+    gets another grid point, and s = a * (1 / c) always reproduces from what is stored."""
     mn, mx = np.array([-1.3], F32), np.array([2.1], F32)
     for scale in (0.125, 0.1, 1.0):
         c = xo.logit_scale_log2(scale)
         a, s, z = xo.quant_params_meta16_k(mn, mx, 4, c)
-        assert s[0] == F32(a[0] / c)
+        assert s[0] == F32(a[0] * F32(F32(1.0) / c))
+        assert abs(float(s[0]) * float(c) / float(a[0]) - 1) < 3e-7
         assert Fraction(float(a[0])) == _ceil_sig(float(F32(F32((mx[0] - mn[0]) / F32(15)) * c)), 7)
 
 
