@@ -42,6 +42,22 @@ enum kv_status {
 
 enum kv_dtype { KV_BF16 = 0, KV_F32 = 1 };
 
+enum kv_meta_format {
+  KV_META_F32 = 0,  /* per group an fp32 scale and an int32 zero-point (8 bytes): the stored values are    */
+                    /* exactly those of Eq. 8                                                              */
+  KV_META_F16 = 1   /* 16-bit scale and 16-bit zero-point (4 bytes per group; INT4 with groups of 64 goes  */
+                    /* from 5.0 to 4.5 bits per element).  The scale is rounded UP to its storage format   */
+                    /* before the zero-point and the codes are computed from it, so the group's range      */
+                    /* stays covered and the s/2 bound of Eq. 7-8 holds for the stored scale.  Keys store  */
+                    /* the scale in the logit domain, a = s * softmax_scale * log2(e), with 7 significant  */
+                    /* bits inside [2^-14, 2048]; Eq. 7 and Eq. 10 use s = a * fp32(1 / (softmax_scale *   */
+                    /* log2 e)).  With 7 bits a * (code - z) is exact in half precision for 2- and 4-bit   */
+                    /* codes, so Eq. 1 needs one matrix instruction per key tile instead of two.  Values   */
+                    /* store s as a half inside [2^-14, 2048].  Zero-points are kept in [-1024, 1023].     */
+                    /* Needs k_bits of 2 or 4 and in_dtype KV_BF16; keys with |k * softmax_scale * log2 e| */
+                    /* >= 65504 are outside its domain.                                                    */
+};
+
 enum kv_mode {
   KV_COMPRESSED = 0,        /* pruned + quantised cache (the paper's method)                */
   KV_UNCOMPRESSED_BF16 = 1  /* baseline: bf16 cache that grows by n tokens per frame,       */
@@ -67,6 +83,7 @@ typedef struct kv_config {
   int32_t mode;             /* kv_mode                                                         */
   int32_t max_frames;       /* KV_UNCOMPRESSED_BF16 only: frames the cache is sized for        */
   float softmax_scale;      /* 0 -> 1/sqrt(head_dim)                                           */
+  int32_t meta_format;      /* kv_meta_format of the quantiser's scales and zero-points        */
 } kv_config;
 
 typedef struct kv_handle kv_handle;
@@ -102,6 +119,8 @@ typedef struct kv_stats_t {
   int64_t zp_range_warnings;     /* quantisation groups written since kv_init whose zero-point    */
                                  /* lies beyond +-2^20: their values sit so far from zero,        */
                                  /* measured in quantisation steps, that Eq. 10 cancels most bits */
+                                 /* (KV_META_F16: groups whose scale or zero-point had to be      */
+                                 /* brought into the 16-bit format's range)                       */
 } kv_stats_t;
 
 /* Host buffers for kv_export; any pointer may be NULL to skip that part. Sizes are in

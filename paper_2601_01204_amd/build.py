@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvx.so")
-SOURCES = ["kvx_api.hip", "attn.hip", "score.hip", "select.hip", "rebuild.hip", "checks.hip", "probe.hip"]
+SOURCES = ["kvx_api.hip", "attn.hip", "attn16.hip", "score.hip", "select.hip", "rebuild.hip", "checks.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -64,6 +64,39 @@ hipError_t static_scratch_address(int device, void** out) {
 
 int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
+// IEEE half <-> float on the host, for the 16-bit metadata format in kv_export / kv_import.  Every value that
+// crosses here is a normal half that the float holds exactly (scales in [2^-14, 2048], integers up to 2047).
+float half_to_float(uint16_t h) {
+  const uint32_t sign = (uint32_t)(h & 0x8000u) << 16, e = (h >> 10) & 0x1Fu, m = h & 0x3FFu;
+  uint32_t u;
+  if (e == 0) {
+    if (m == 0) {
+      u = sign;
+    } else {                       // subnormal half: value m * 2^-24
+      const float v = (float)m * 0x1p-24f;
+      memcpy(&u, &v, 4);
+      u |= sign;
+    }
+  } else if (e == 31) {
+    u = sign | 0x7F800000u | (m << 13);
+  } else {
+    u = sign | ((e + 112u) << 23) | (m << 13);
+  }
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+// Exact conversion or failure: true and *out set when f is a normal half (or zero).
+bool float_to_half_exact(float f, uint16_t* out) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  const uint32_t sign = (u >> 16) & 0x8000u, e = (u >> 23) & 0xFFu, m = u & 0x7FFFFFu;
+  if (e == 0 && m == 0) { *out = (uint16_t)sign; return true; }
+  if (e < 113 || e > 142 || (m & 0x1FFFu)) return false;
+  *out = (uint16_t)(sign | ((e - 112u) << 10) | (m >> 13));
+  return true;
+}
+
 }  // namespace
 
 struct kv_handle {
@@ -125,6 +158,12 @@ int validate(const kv_config* c) {
   if (c->in_dtype != KV_BF16 && c->in_dtype != KV_F32) return fail(nullptr, KV_E_INVAL, "kv_init: in_dtype must be KV_BF16 or KV_F32");
   if (c->out_dtype != KV_BF16 && c->out_dtype != KV_F32) return fail(nullptr, KV_E_INVAL, "kv_init: out_dtype must be KV_BF16 or KV_F32");
   if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return fail(nullptr, KV_E_INVAL, "kv_init: softmax_scale must be finite and >= 0");
+  if (c->meta_format != KV_META_F32 && c->meta_format != KV_META_F16) return fail(nullptr, KV_E_INVAL, "kv_init: meta_format must be KV_META_F32 or KV_META_F16");
+  if (c->meta_format == KV_META_F16) {
+    if (c->mode != KV_COMPRESSED) return fail(nullptr, KV_E_INVAL, "kv_init: KV_META_F16 applies to the compressed cache only");
+    if (c->k_bits != 2 && c->k_bits != 4) return fail(nullptr, KV_E_INVAL, "kv_init: KV_META_F16 needs k_bits of 2 or 4 (the key products are exact in half precision up to 4-bit codes)");
+    if (c->in_dtype != KV_BF16) return fail(nullptr, KV_E_INVAL, "kv_init: KV_META_F16 needs in_dtype KV_BF16");
+  }
   if (c->mode == KV_COMPRESSED) {
     if ((int64_t)c->budget_tokens < 2 * (int64_t)c->tokens_per_frame)
       return fail(nullptr, KV_E_INVAL, "kv_init: budget_tokens must be >= 2 * tokens_per_frame (first and current frame are always kept)");
@@ -239,6 +278,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   g.in_f32 = c.in_dtype == KV_F32;
   g.out_f32 = c.out_dtype == KV_F32;
   g.uncompressed = unc;
+  g.meta16 = c.meta_format == KV_META_F16;
   {
     // an attention workgroup holds up to 12 waves, one 32-row query block each
     const int nblocks = (g.n + 31) / 32;
@@ -249,16 +289,18 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   }
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / std::sqrt((float)kHeadDim);
   g.scale_log2 = scale * 1.4426950408889634f;
+  g.inv_scale_log2 = 1.0f / g.scale_log2;
 
   // one half of a cache
   CacheLayout& L = g.lay;
   int64_t off = 0;
   const int64_t k_row = (int64_t)kHeadDim * g.k_bits / 8, v_row = (int64_t)kHeadDim * g.v_bits / 8;
   L.k_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * k_row, 256);
-  L.k_scale = off; off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
-  L.k_zero = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * 4), 256);
+  const int64_t k_meta_elt = g.meta16 ? 2 : 4, v_meta_elt = g.meta16 ? 4 : (int64_t)sizeof(VMeta);
+  L.k_scale = off; off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * k_meta_elt), 256);
+  L.k_zero = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.g_cap * kHeadDim * k_meta_elt), 256);
   L.v_codes = off; off = align_up(off + (int64_t)g.H * g.t_cap * v_row, 256);
-  L.v_meta = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * (int64_t)sizeof(VMeta)), 256);
+  L.v_meta = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * v_meta_elt), 256);
   L.ids = off;     off = align_up(off + (int64_t)g.t_cap * 4, 256);
   L.half_bytes = off;
   L.cache_bytes = unc ? off : 2 * off;
@@ -445,7 +487,8 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t 
       // and end, so the figure is the kernel's duration as a kernel trace reports it
       hipEvent_t e0 = nullptr, e1 = nullptr;
       timed_pair(h, KV_K_ATTENTION, &e0, &e1);
-      launch_attention(b, 0, st, e0, e1);
+      if (g0.meta16) launch_attention16(b, st, e0, e1);
+      else launch_attention(b, 0, st, e0, e1);
     }
     record(h, KV_K_COMBINE, true, st);
     launch_combine(b, st);
@@ -530,9 +573,10 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
   memset(s, 0, sizeof *s);
   s->bytes_allocated = h->bytes_arena + h->bytes_scratch + h->bytes_part;
   s->bytes_k_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.k_bits / 8);
-  s->bytes_k_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.g_cap * (kHeadDim * 8));
+  const int64_t meta_bytes = g.meta16 ? 4 : 8;      // scale + zero-point of one group
+  s->bytes_k_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.g_cap * (kHeadDim * meta_bytes));
   s->bytes_v_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.v_bits / 8);
-  s->bytes_v_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * 8);
+  s->bytes_v_meta = g.uncompressed ? 0 : nc * halves * ((int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * meta_bytes);
   s->bytes_ids = nc * halves * (int64_t)g.t_cap * 4;
   s->bytes_scratch = h->bytes_scratch + h->bytes_part;
   s->n_caches = (int32_t)nc;
@@ -559,8 +603,8 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
     s->bytes_live_per_cache = 2 * (int64_t)g.H * T * kHeadDim * 2;
   } else {
     const int64_t groups = (T + g.k_group - 1) / g.k_group;
-    s->bytes_live_per_cache = (int64_t)g.H * T * kHeadDim * g.k_bits / 8 + (int64_t)g.H * groups * (kHeadDim * 8) +
-                              (int64_t)g.H * T * kHeadDim * g.v_bits / 8 + (int64_t)g.H * T * (kHeadDim / g.v_group) * 8 + T * 4;
+    s->bytes_live_per_cache = (int64_t)g.H * T * kHeadDim * g.k_bits / 8 + (int64_t)g.H * groups * (kHeadDim * meta_bytes) +
+                              (int64_t)g.H * T * kHeadDim * g.v_bits / 8 + (int64_t)g.H * T * (kHeadDim / g.v_group) * meta_bytes + T * 4;
   }
   return KV_OK;
 }
@@ -603,6 +647,34 @@ int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* x) {
   };
   if (x->k_codes) unpack(x->k_codes, g.lay.k_codes, g.k_bits);
   if (x->v_codes) unpack(x->v_codes, g.lay.v_codes, g.v_bits);
+  if (g.meta16) {
+    // halfs in the device order of every eight channels; s = a * fp32(1 / scale_log2), z = zz - 1024
+    std::vector<uint16_t> tmp((size_t)G * kHeadDim);
+    for (int hh = 0; hh < H && ok; ++hh) {
+      if (x->k_scale) {
+        ok &= d2h(tmp.data(), half + g.lay.k_scale + (int64_t)hh * g.g_cap * kHeadDim * 2, tmp.size() * 2);
+        for (int gi = 0; gi < G; ++gi)
+          for (int ch = 0; ch < kHeadDim; ++ch)
+            x->k_scale[((int64_t)hh * G + gi) * kHeadDim + ch] = half_to_float(tmp[(size_t)gi * kHeadDim + meta16_pos(ch)]) * g.inv_scale_log2;
+      }
+      if (x->k_zero) {
+        ok &= d2h(tmp.data(), half + g.lay.k_zero + (int64_t)hh * g.g_cap * kHeadDim * 2, tmp.size() * 2);
+        for (int gi = 0; gi < G; ++gi)
+          for (int ch = 0; ch < kHeadDim; ++ch)
+            x->k_zero[((int64_t)hh * G + gi) * kHeadDim + ch] = (int32_t)half_to_float(tmp[(size_t)gi * kHeadDim + meta16_pos(ch)]) - 1024;
+      }
+    }
+    if (x->v_scale || x->v_zero) {
+      std::vector<uint32_t> vt((size_t)T * ngv);
+      for (int hh = 0; hh < H && ok; ++hh) {
+        ok &= d2h(vt.data(), half + g.lay.v_meta + (int64_t)hh * g.t_cap * ngv * 4, vt.size() * 4);
+        for (size_t i = 0; i < vt.size(); ++i) {
+          if (x->v_scale) x->v_scale[(size_t)hh * T * ngv + i] = half_to_float((uint16_t)(vt[i] & 0xFFFFu));
+          if (x->v_zero) x->v_zero[(size_t)hh * T * ngv + i] = (int32_t)half_to_float((uint16_t)(vt[i] >> 16)) - 1024;
+        }
+      }
+    }
+  } else {
   for (int hh = 0; hh < H && ok; ++hh) {
     if (x->k_scale) ok &= d2h(x->k_scale + (int64_t)hh * G * kHeadDim, half + g.lay.k_scale + (int64_t)hh * g.g_cap * kHeadDim * 4, (size_t)G * kHeadDim * 4);
     if (x->k_zero) ok &= d2h(x->k_zero + (int64_t)hh * G * kHeadDim, half + g.lay.k_zero + (int64_t)hh * g.g_cap * kHeadDim * 4, (size_t)G * kHeadDim * 4);
@@ -616,6 +688,7 @@ int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* x) {
         if (x->v_zero) x->v_zero[(size_t)hh * T * ngv + i] = tmp[i].z;
       }
     }
+  }
   }
   if (cs.last_pruned) {
     if (x->last_keep) ok &= d2h(x->last_keep, sc + g.sl.keep, (size_t)g.budget * 4);
@@ -657,10 +730,44 @@ int kv_import(kv_handle* h, int32_t stream, int32_t layer, const kv_export_t* x)
   std::vector<uint8_t> kc, vc;
   if (!pack(x->k_codes, g.k_bits, kc)) return fail(h, KV_E_INVAL, "kv_import: a key code does not fit %d bits", g.k_bits);
   if (!pack(x->v_codes, g.v_bits, vc)) return fail(h, KV_E_INVAL, "kv_import: a value code does not fit %d bits", g.v_bits);
-  std::vector<VMeta> vm((size_t)H * T * ngv);
-  for (size_t i = 0; i < vm.size(); ++i) {
-    vm[i].s = x->v_scale[i];
-    vm[i].z = x->v_zero[i];
+  std::vector<VMeta> vm;
+  std::vector<uint16_t> ka, kz;       // 16-bit metadata format: halfs in device order
+  std::vector<uint32_t> vm16;
+  if (g.meta16) {
+    // the stored half scale is recovered from the fp32 scale the export gave: a = s * scale_log2 to the nearest
+    // 7-bit value, accepted only if it reproduces s exactly
+    ka.assign((size_t)H * G * kHeadDim, 0);
+    kz.assign((size_t)H * G * kHeadDim, 0);
+    for (int hh = 0; hh < H; ++hh)
+      for (int gi = 0; gi < G; ++gi)
+        for (int ch = 0; ch < kHeadDim; ++ch) {
+          const size_t src = ((size_t)hh * G + gi) * kHeadDim + ch, dst = ((size_t)hh * G + gi) * kHeadDim + meta16_pos(ch);
+          const float sv = x->k_scale[src];
+          float a = sv * g.scale_log2;
+          uint32_t u;
+          memcpy(&u, &a, 4);
+          u = (u + 0x10000u) & 0xFFFE0000u;               // nearest value with 7 significant bits
+          memcpy(&a, &u, 4);
+          const int32_t z = x->k_zero[src];
+          if (!(a >= kMeta16ScaleMin && a <= kMeta16ScaleMax) || a * g.inv_scale_log2 != sv || !float_to_half_exact(a, &ka[dst]) ||
+              z < kMeta16ZMin || z > kMeta16ZMax || !float_to_half_exact((float)(1024 + z), &kz[dst]))
+            return fail(h, KV_E_INVAL, "kv_import: key scale or zero-point (head %d, group %d, channel %d) is not a value of the 16-bit metadata format", hh, gi, ch);
+        }
+    vm16.assign((size_t)H * T * ngv, 0);
+    for (size_t i = 0; i < vm16.size(); ++i) {
+      uint16_t hs, hz;
+      const int32_t z = x->v_zero[i];
+      if (!(x->v_scale[i] >= kMeta16ScaleMin && x->v_scale[i] <= kMeta16ScaleMax) || !float_to_half_exact(x->v_scale[i], &hs) ||
+          z < kMeta16ZMin || z > kMeta16ZMax || !float_to_half_exact((float)(1024 + z), &hz))
+        return fail(h, KV_E_INVAL, "kv_import: value scale or zero-point %lld is not a value of the 16-bit metadata format", (long long)i);
+      vm16[i] = (uint32_t)hs | ((uint32_t)hz << 16);
+    }
+  } else {
+    vm.assign((size_t)H * T * ngv, VMeta());
+    for (size_t i = 0; i < vm.size(); ++i) {
+      vm[i].s = x->v_scale[i];
+      vm[i].z = x->v_zero[i];
+    }
   }
   if (hipDeviceSynchronize() != hipSuccess) return fail(h, KV_E_HIP, "kv_import: %s", hipGetErrorString(hipGetLastError()));
   const size_t ci = (size_t)stream * c.n_layers + layer;
@@ -671,9 +778,15 @@ int kv_import(kv_handle* h, int32_t stream, int32_t layer, const kv_export_t* x)
   for (int hh = 0; hh < H && ok; ++hh) {
     ok &= h2d(half + g.lay.k_codes + (int64_t)hh * g.t_cap * krow, kc.data() + (size_t)hh * T * krow, (size_t)T * krow);
     ok &= h2d(half + g.lay.v_codes + (int64_t)hh * g.t_cap * vrow, vc.data() + (size_t)hh * T * vrow, (size_t)T * vrow);
-    ok &= h2d(half + g.lay.k_scale + (int64_t)hh * g.g_cap * kHeadDim * 4, x->k_scale + (int64_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 4);
-    ok &= h2d(half + g.lay.k_zero + (int64_t)hh * g.g_cap * kHeadDim * 4, x->k_zero + (int64_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 4);
-    ok &= h2d(half + g.lay.v_meta + (int64_t)hh * g.t_cap * ngv * sizeof(VMeta), vm.data() + (size_t)hh * T * ngv, (size_t)T * ngv * sizeof(VMeta));
+    if (g.meta16) {
+      ok &= h2d(half + g.lay.k_scale + (int64_t)hh * g.g_cap * kHeadDim * 2, ka.data() + (size_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 2);
+      ok &= h2d(half + g.lay.k_zero + (int64_t)hh * g.g_cap * kHeadDim * 2, kz.data() + (size_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 2);
+      ok &= h2d(half + g.lay.v_meta + (int64_t)hh * g.t_cap * ngv * 4, vm16.data() + (size_t)hh * T * ngv, (size_t)T * ngv * 4);
+    } else {
+      ok &= h2d(half + g.lay.k_scale + (int64_t)hh * g.g_cap * kHeadDim * 4, x->k_scale + (int64_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 4);
+      ok &= h2d(half + g.lay.k_zero + (int64_t)hh * g.g_cap * kHeadDim * 4, x->k_zero + (int64_t)hh * G * kHeadDim, (size_t)G * kHeadDim * 4);
+      ok &= h2d(half + g.lay.v_meta + (int64_t)hh * g.t_cap * ngv * sizeof(VMeta), vm.data() + (size_t)hh * T * ngv, (size_t)T * ngv * sizeof(VMeta));
+    }
   }
   if (!ok) {
     h->caches[ci] = CacheState();       // partly written: the cache is empty rather than inconsistent

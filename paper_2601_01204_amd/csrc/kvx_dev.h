@@ -13,18 +13,26 @@ constexpr int kQTileMax = 384;      // most query rows per attention workgroup (
 constexpr int kMaxItems = 48;       // caches per launch (bounded by the kernel-argument size)
 constexpr int kMaxSplits = 16;      // key-range splits per attention workgroup column
 
-struct VMeta {                      // per (head, token, channel group) value metadata
+struct VMeta {                      // per (head, token, channel group) value metadata, fp32 metadata format
   float s;
   int32_t z;
 };
+// 16-bit metadata format.  Keys: two arrays of halfs, the logit-domain scale a = s * scale_log2 (7 significant
+// bits) and zz = 1024 + z; within every eight channels the halfs are stored in the order 0 4 1 5 2 6 3 7 (the
+// order in which the attention kernel's packed unpacking of a code word produces channel pairs).  Values: one
+// 32-bit word per (head, token, channel group), low half the scale s, high half zz = 1024 + z.
+constexpr float kMeta16ScaleMin = 0x1p-14f;   // smallest normal half
+constexpr float kMeta16ScaleMax = 2048.0f;
+constexpr int kMeta16ZMin = -1024, kMeta16ZMax = 1023;
+__host__ __device__ __forceinline__ int meta16_pos(int c) { return (c & ~7) | ((c & 3) << 1) | ((c >> 2) & 1); }
 
 // Byte offsets of the parts of one half of a cache's double buffer.
 struct CacheLayout {
   int64_t k_codes;    // [H][t_cap][d * k_bits / 8]
-  int64_t k_scale;    // [H][g_cap][d] float
-  int64_t k_zero;     // [H][g_cap][d] int32
+  int64_t k_scale;    // [H][g_cap][d] float (16-bit metadata: half, logit-domain scale)
+  int64_t k_zero;     // [H][g_cap][d] int32 (16-bit metadata: half, 1024 + z)
   int64_t v_codes;    // [H][t_cap][d * v_bits / 8]
-  int64_t v_meta;     // [H][t_cap][d / v_group] VMeta
+  int64_t v_meta;     // [H][t_cap][d / v_group] VMeta (16-bit metadata: uint32)
   int64_t ids;        // [t_cap] int32
   int64_t half_bytes; // size of one half
   int64_t cache_bytes;// both halves
@@ -70,6 +78,8 @@ struct Geometry {
   int32_t n_qtiles;       // query tiles (attention workgroups per head and key split)
   int32_t q_blocks;       // 32-row query blocks per tile (<= 12, one per wave)
   float scale_log2;       // softmax scale * log2(e)
+  float inv_scale_log2;   // fp32(1 / scale_log2): s = a * inv_scale_log2 in the 16-bit metadata format
+  int32_t meta16;         // 1: 16-bit scales and zero-points
 };
 
 struct Item {
@@ -103,6 +113,7 @@ __device__ __forceinline__ uint8_t* cache_scratch(const Geometry& g, int cache) 
 
 // ---- launchers (each enqueues on `st`, never synchronises) ----------------------
 void launch_attention(const KvxBatch& b, int max_tiles, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+void launch_attention16(const KvxBatch& b, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void launch_combine(const KvxBatch& b, hipStream_t st);
 void launch_pool(const KvxBatch& b, hipStream_t st);
 void launch_score(const KvxBatch& b, int max_tc, hipStream_t st);

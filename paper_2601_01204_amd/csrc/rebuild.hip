@@ -10,6 +10,7 @@
 #include "kvx_dev.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace kvx {
 
@@ -19,6 +20,45 @@ __device__ __forceinline__ void quant_params(float mn, float mx, int levels, flo
   s = (mx - mn) / (float)levels;
   if (mx == mn) s = (mn != 0.f) ? fabsf(mn) : 1.0f;
   z = (int32_t)rintf((-mn) / s);
+}
+
+// 16-bit metadata format (Eq. 8 with the scale rounded up to its storage format first).
+__device__ __forceinline__ float half_bits_to_f32(uint32_t h16) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h16); }
+__device__ __forceinline__ uint16_t f32_to_half_bits(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }   // exact for the values stored here
+// smallest fp32 >= x (x > 0) with at most 24 - drop significant bits
+__device__ __forceinline__ float round_up_drop(float x, int drop) {
+  uint32_t u = __float_as_uint(x);
+  const uint32_t mask = (1u << drop) - 1u;
+  if (u & mask) u = (u | mask) + 1u;
+  return __uint_as_float(u);
+}
+__device__ __forceinline__ float clamp_scale16(float a, bool& clipped) {
+  clipped = !(a >= kMeta16ScaleMin && a <= kMeta16ScaleMax);
+  return fminf(fmaxf(a, kMeta16ScaleMin), kMeta16ScaleMax);
+}
+__device__ __forceinline__ int32_t zero_point16(float mn, float s, bool& clipped) {
+  const float zf = rintf((-mn) / s);
+  clipped = !(zf >= (float)kMeta16ZMin && zf <= (float)kMeta16ZMax);
+  return (int32_t)fminf(fmaxf(zf, (float)kMeta16ZMin), (float)kMeta16ZMax);
+}
+// keys: a = s_raw * scale_log2 rounded up to 7 significant bits; s = a * inv_scale_log2
+__device__ __forceinline__ void quant_params16_k(float mn, float mx, int levels, float c_log2, float inv_c, float& a, float& s, int32_t& z, bool& clipped) {
+  float s_raw = (mx - mn) / (float)levels;
+  if (mx == mn) s_raw = (mn != 0.f) ? fabsf(mn) : 1.0f;
+  bool c0, c1;
+  a = clamp_scale16(round_up_drop(s_raw * c_log2, 17), c0);
+  s = a * inv_c;
+  z = zero_point16(mn, s, c1);
+  clipped = c0 || c1;
+}
+// values: s rounded up to a half (11 significant bits)
+__device__ __forceinline__ void quant_params16_v(float mn, float mx, int levels, float& s, int32_t& z, bool& clipped) {
+  float s_raw = (mx - mn) / (float)levels;
+  if (mx == mn) s_raw = (mn != 0.f) ? fabsf(mn) : 1.0f;
+  bool c0, c1;
+  s = clamp_scale16(round_up_drop(s_raw, 13), c0);
+  z = zero_point16(mn, s, c1);
+  clipped = c0 || c1;
 }
 
 __device__ __forceinline__ int quant_code(float x, float s, int32_t z, int levels) {
@@ -138,7 +178,7 @@ __device__ __forceinline__ void load_input16(const void* base, int64_t off, int 
 // same ordered members as before and is copied verbatim; every other group is rebuilt
 // from the fp32 values of its members: de-quantised codes for surviving tokens, input
 // values for the new frame.
-template <int B>
+template <int B, bool M16>
 __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.z];
@@ -179,7 +219,23 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
     const int src = it.prune ? keep[p] : p;
     if (src < t_c) {
       unpack16<B>(cur + g.lay.k_codes + ((int64_t)h * g.t_cap + src) * kRow + cb * 2 * B, wsrc);
-      if (!carried) {
+      if (!carried && M16) {
+        // 16 halfs each of logit-domain scales and 1024 + z, stored in the 0 4 1 5 2 6 3 7 order of every eight channels
+        const int sg = src >> k_shift;
+        const int64_t moff = ((int64_t)h * g.g_cap + sg) * kHeadDim + cb * 16;
+        const uint4* ap = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(cur + g.lay.k_scale) + moff);
+        const uint4* zp = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(cur + g.lay.k_zero) + moff);
+        const uint4 a0 = ap[0], a1 = ap[1], z0 = zp[0], z1 = zp[1];
+        const uint32_t aw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        const uint32_t zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int pos = meta16_pos(e);                       // half index among the 16
+          const float sv = half_bits_to_f32((aw[pos >> 1] >> (16 * (pos & 1))) & 0xFFFFu) * g.inv_scale_log2;
+          const float zf = half_bits_to_f32((zw[pos >> 1] >> (16 * (pos & 1))) & 0xFFFFu) - 1024.0f;
+          x[e] = sv * ((float)code16<B>(wsrc, e) - zf);
+        }
+      } else if (!carried) {
         const int sg = src >> k_shift;
         const int64_t moff = ((int64_t)h * g.g_cap + sg) * kHeadDim + cb * 16;
         const float4* sp = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(cur + g.lay.k_scale) + moff);
@@ -235,12 +291,29 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
     const int ggrp = (p0 >> k_shift) + gi;
     const int first_row = gi << k_shift;
     if (p0 + first_row < t_new) {
-      const int64_t moff = ((int64_t)h * g.g_cap + ggrp) * kHeadDim + c;
-      float s;
+      const int64_t moff = ((int64_t)h * g.g_cap + ggrp) * kHeadDim + (M16 ? meta16_pos(c) : c);
+      float s, a16 = 0.f;
       int32_t z;
       if (ggrp < g0) {
-        s = reinterpret_cast<const float*>(cur + g.lay.k_scale)[moff];
-        z = reinterpret_cast<const int32_t*>(cur + g.lay.k_zero)[moff];
+        if constexpr (M16) {
+          a16 = half_bits_to_f32(reinterpret_cast<const uint16_t*>(cur + g.lay.k_scale)[moff]);
+          s = a16 * g.inv_scale_log2;
+          z = (int32_t)half_bits_to_f32(reinterpret_cast<const uint16_t*>(cur + g.lay.k_zero)[moff]) - 1024;
+        } else {
+          s = reinterpret_cast<const float*>(cur + g.lay.k_scale)[moff];
+          z = reinterpret_cast<const int32_t*>(cur + g.lay.k_zero)[moff];
+        }
+      } else if constexpr (M16) {
+        const int q_lo = first_row >> 4, q_hi = (first_row + g.k_group) >> 4;
+        float mn = INFINITY, mx = -INFINITY;
+        for (int qq = q_lo; qq < q_hi; ++qq) {
+          mn = fminf(mn, pmin[qq][c]);
+          mx = fmaxf(mx, pmax[qq][c]);
+        }
+        bool clipped;
+        quant_params16_k(mn, mx, levels, g.scale_log2, g.inv_scale_log2, a16, s, z, clipped);
+        if (h == 0 && c == 0) atomicAdd(&sel[2], 1);
+        if (clipped) atomicAdd(&sel[5], 1);
       } else {
         const int q_lo = first_row >> 4, q_hi = (first_row + g.k_group) >> 4;
         float mn = INFINITY, mx = -INFINITY;
@@ -257,8 +330,13 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
       gr[gi][c] = dv.r;
       gz[gi][c] = z;
       if (!dv.safe) unsafe_scales = 1;
-      reinterpret_cast<float*>(nxt + g.lay.k_scale)[moff] = s;
-      reinterpret_cast<int32_t*>(nxt + g.lay.k_zero)[moff] = z;
+      if constexpr (M16) {
+        reinterpret_cast<uint16_t*>(nxt + g.lay.k_scale)[moff] = f32_to_half_bits(a16);
+        reinterpret_cast<uint16_t*>(nxt + g.lay.k_zero)[moff] = f32_to_half_bits((float)(1024 + z));
+      } else {
+        reinterpret_cast<float*>(nxt + g.lay.k_scale)[moff] = s;
+        reinterpret_cast<int32_t*>(nxt + g.lay.k_zero)[moff] = z;
+      }
     }
   }
   __syncthreads();
@@ -302,7 +380,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
 // per row, and the row's metadata) and quantise blocks (64 new tokens per block, four
 // lanes per token).
 
-template <int B>
+template <int B, bool M16>
 __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_copy_blocks) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.z];
@@ -324,8 +402,9 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_
     if (p >= t_keep) return;
     const int src = it.prune ? keep[p] : p;
     const uint4 w = *reinterpret_cast<const uint4*>(cur + g.lay.v_codes + ((int64_t)h * g.t_cap + src) * kRow + part * 16);
-    const VMeta* ms = reinterpret_cast<const VMeta*>(cur + g.lay.v_meta) + ((int64_t)h * g.t_cap + src) * ngv;
-    VMeta* md = reinterpret_cast<VMeta*>(nxt + g.lay.v_meta) + ((int64_t)h * g.t_cap + p) * ngv;
+    typedef typename std::conditional<M16, uint32_t, VMeta>::type MetaT;
+    const MetaT* ms = reinterpret_cast<const MetaT*>(cur + g.lay.v_meta) + ((int64_t)h * g.t_cap + src) * ngv;
+    MetaT* md = reinterpret_cast<MetaT*>(nxt + g.lay.v_meta) + ((int64_t)h * g.t_cap + p) * ngv;
     if (kLanes == 1) {
       md[0] = ms[0];
       if (ngv == 2) md[1] = ms[1];
@@ -367,19 +446,29 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_
   if (!active) return;
   float s;
   int32_t z;
-  quant_params(mn, mx, levels, s, z);
+  bool warn;
+  if constexpr (M16) {
+    quant_params16_v(mn, mx, levels, s, z, warn);
+  } else {
+    quant_params(mn, mx, levels, s, z);
+    warn = z > kZeroPointWarn || z < -kZeroPointWarn;
+  }
   int code[16];
   const Divider dv = make_divider(s);
 #pragma unroll
   for (int e = 0; e < 16; ++e) code[e] = quant_code_div(x[e], dv, z, levels);
   pack16<B>(code, nxt + g.lay.v_codes + ((int64_t)h * g.t_cap + p) * kRow + cb * 2 * B);
   if ((cb % lanes_per_group) == 0) {
-    if (z > kZeroPointWarn || z < -kZeroPointWarn)
-      atomicAdd(reinterpret_cast<int32_t*>(cache_scratch(g, it.cache) + g.sl.sel) + 5, 1);
-    VMeta m;
-    m.s = s;
-    m.z = z;
-    reinterpret_cast<VMeta*>(nxt + g.lay.v_meta)[((int64_t)h * g.t_cap + p) * ngv + gv] = m;
+    if (warn) atomicAdd(reinterpret_cast<int32_t*>(cache_scratch(g, it.cache) + g.sl.sel) + 5, 1);
+    if constexpr (M16) {
+      reinterpret_cast<uint32_t*>(nxt + g.lay.v_meta)[((int64_t)h * g.t_cap + p) * ngv + gv] =
+          (uint32_t)f32_to_half_bits(s) | ((uint32_t)f32_to_half_bits((float)(1024 + z)) << 16);
+    } else {
+      VMeta m;
+      m.s = s;
+      m.z = z;
+      reinterpret_cast<VMeta*>(nxt + g.lay.v_meta)[((int64_t)h * g.t_cap + p) * ngv + gv] = m;
+    }
   }
   if (h == 0 && cb == 0) reinterpret_cast<int32_t*>(nxt + g.lay.ids)[p] = it.frame * g.n + i_new;
 }
@@ -422,10 +511,15 @@ __global__ __launch_bounds__(256) void append_bf16_kernel(const KvxBatch b) {
 
 void launch_rebuild_k(const KvxBatch& b, int max_tnew, hipStream_t st) {
   dim3 grid((max_tnew + kTileK - 1) / kTileK, b.g.H, b.n_items);
+  if (b.g.meta16) {
+    if (b.g.k_bits == 2) hipLaunchKernelGGL((rebuild_k_kernel<2, true>), grid, dim3(256), 0, st, b);
+    else hipLaunchKernelGGL((rebuild_k_kernel<4, true>), grid, dim3(256), 0, st, b);
+    return;
+  }
   switch (b.g.k_bits) {
-    case 2: hipLaunchKernelGGL(rebuild_k_kernel<2>, grid, dim3(256), 0, st, b); break;
-    case 4: hipLaunchKernelGGL(rebuild_k_kernel<4>, grid, dim3(256), 0, st, b); break;
-    default: hipLaunchKernelGGL(rebuild_k_kernel<8>, grid, dim3(256), 0, st, b); break;
+    case 2: hipLaunchKernelGGL((rebuild_k_kernel<2, false>), grid, dim3(256), 0, st, b); break;
+    case 4: hipLaunchKernelGGL((rebuild_k_kernel<4, false>), grid, dim3(256), 0, st, b); break;
+    default: hipLaunchKernelGGL((rebuild_k_kernel<8, false>), grid, dim3(256), 0, st, b); break;
   }
 }
 
@@ -433,10 +527,18 @@ void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st) {
   const int rows_per_block = 256 / (b.g.v_bits / 2);           // 16 bytes of codes per lane
   const int n_copy_blocks = (std::max(max_tnew - b.g.n, 0) + rows_per_block - 1) / rows_per_block;
   dim3 grid(n_copy_blocks + (b.g.n + kTileK - 1) / kTileK, b.g.H, b.n_items);
+  if (b.g.meta16) {
+    switch (b.g.v_bits) {
+      case 2: hipLaunchKernelGGL((rebuild_v_kernel<2, true>), grid, dim3(256), 0, st, b, n_copy_blocks); break;
+      case 4: hipLaunchKernelGGL((rebuild_v_kernel<4, true>), grid, dim3(256), 0, st, b, n_copy_blocks); break;
+      default: hipLaunchKernelGGL((rebuild_v_kernel<8, true>), grid, dim3(256), 0, st, b, n_copy_blocks); break;
+    }
+    return;
+  }
   switch (b.g.v_bits) {
-    case 2: hipLaunchKernelGGL(rebuild_v_kernel<2>, grid, dim3(256), 0, st, b, n_copy_blocks); break;
-    case 4: hipLaunchKernelGGL(rebuild_v_kernel<4>, grid, dim3(256), 0, st, b, n_copy_blocks); break;
-    default: hipLaunchKernelGGL(rebuild_v_kernel<8>, grid, dim3(256), 0, st, b, n_copy_blocks); break;
+    case 2: hipLaunchKernelGGL((rebuild_v_kernel<2, false>), grid, dim3(256), 0, st, b, n_copy_blocks); break;
+    case 4: hipLaunchKernelGGL((rebuild_v_kernel<4, false>), grid, dim3(256), 0, st, b, n_copy_blocks); break;
+    default: hipLaunchKernelGGL((rebuild_v_kernel<8, false>), grid, dim3(256), 0, st, b, n_copy_blocks); break;
   }
 }
 

@@ -139,9 +139,16 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
     const int gi = i >> 6, c = i & 63;
     const int grp = grp0 + gi;
     if (grp < g.g_cap) {
-      const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + c;
-      s_s[gi][c] = reinterpret_cast<const float*>(half + g.lay.k_scale)[moff];
-      s_z[gi][c] = reinterpret_cast<const int32_t*>(half + g.lay.k_zero)[moff];
+      if (g.meta16) {
+        // halfs: logit-domain scale a (s = a * fp32(1 / scale_log2)) and 1024 + z, channels of an octet in the order 0 4 1 5 2 6 3 7
+        const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + meta16_pos(c);
+        s_s[gi][c] = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(half + g.lay.k_scale)[moff]) * g.inv_scale_log2;
+        s_z[gi][c] = (int32_t)(float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(half + g.lay.k_zero)[moff]) - 1024;
+      } else {
+        const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + c;
+        s_s[gi][c] = reinterpret_cast<const float*>(half + g.lay.k_scale)[moff];
+        s_z[gi][c] = reinterpret_cast<const int32_t*>(half + g.lay.k_zero)[moff];
+      }
     }
   }
   if (threadIdx.x < 64) s_q[threadIdx.x] = reinterpret_cast<const float*>(cache_scratch(g, it.cache) + g.sl.qt)[threadIdx.x];

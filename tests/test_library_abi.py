@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 def _cfg(**kw):
     base = dict(n_streams=1, n_layers=1, n_heads=4, head_dim=64, tokens_per_frame=69, n_special=5, pool_group=16,
                 budget_tokens=256, k_bits=4, k_group=64, v_bits=4, v_group=64, in_dtype=kvx.KV_BF16,
-                out_dtype=kvx.KV_BF16, mode=kvx.KV_COMPRESSED, max_frames=0, softmax_scale=0.0)
+                out_dtype=kvx.KV_BF16, mode=kvx.KV_COMPRESSED, max_frames=0, softmax_scale=0.0, meta_format=0)
     base.update(kw)
     c = kvx.KvConfig()
     for k, v in base.items():
@@ -56,6 +56,9 @@ def _cfg(**kw):
     (dict(softmax_scale=-1.0), -1),
     (dict(n_streams=0), -1),
     (dict(budget_tokens=40000), -3),
+    (dict(meta_format=2), -1),
+    (dict(meta_format=1, k_bits=8), -1),          # 16-bit metadata: 2- or 4-bit keys
+    (dict(meta_format=1, in_dtype=kvx.KV_F32), -1),
 ])
 def test_bad_configurations_are_rejected_with_a_message(bad, code):
     lib = kvx.load_library()
