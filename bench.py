@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel come from a rocprofv3 --pmc run whose summary and figures are
 # tracked in profiles/; the file names the sources it was measured on, and a stale file yields traffic = null.
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attn_kernel_vggt_stack_traffic.json")
-KERNEL_SOURCES = ("attn.hip", "kvx_api.hip", "kvx_dev.h")
+KERNEL_SOURCES = ("attn.hip", "attn16.hip", "kvx_api.hip", "kvx_dev.h")
 
 
 def kernel_source_hash() -> str:
@@ -146,9 +146,9 @@ def kernel_times(run, steps):
     return {k: v[0] * 1e3 / v[1] for k, v in tm.items() if v[1]}
 
 
-def hbm_report(w, n_caches_per_launch, us):
+def hbm_report(w, n_caches_per_launch, us, meta_bytes=8):
     out = {}
-    for name, nbytes in alg_bytes(w).items():
+    for name, nbytes in alg_bytes(w, meta_bytes).items():
         if name in us:
             gbs = n_caches_per_launch * nbytes / (us[name] * 1e-6) / 1e9
             out[name] = {"us": round(us[name], 2), "bytes": int(n_caches_per_launch * nbytes), "GB/s": round(gbs, 1),
@@ -156,7 +156,7 @@ def hbm_report(w, n_caches_per_launch, us):
     return out
 
 
-def oracle_baseline(torch, run, frames_total, steady):
+def oracle_baseline(torch, run, frames_total, steady, meta16=False):
     """The CPU oracle as it stands, timed on this host on one layer cache of the same stream (the frames the GPU's
     layer 0 was fed, copied back): frames 0..frames_total-1, the last `steady` of them with the cache full.  The
     24-layer rate is one over 24 times the steady per-layer step time (the oracle's layers are independent)."""
@@ -169,7 +169,7 @@ def oracle_baseline(torch, run, frames_total, steady):
         threads = os.cpu_count() or 1
     w = run.w
     cfg = xo.OracleConfig(w.n_heads, w.head_dim, w.tokens_per_frame, w.n_special, w.pool_group, w.budget_tokens,
-                          w.k_bits, w.k_group, w.v_bits, w.v_group)
+                          w.k_bits, w.k_group, w.v_bits, w.v_group, meta16=meta16)
     cache = xo.OracleCache(cfg)
     q, k, v = run.frames[0]
     times = []
@@ -291,6 +291,8 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="run the cache update after attention instead of beside it")
     ap.add_argument("--no-aux", action="store_true", help="skip the other configurations (one layer, long stream, high-resolution multi-stream)")
     ap.add_argument("--long-frames", type=int, default=1000, help="frames of the long-stream run in aux")
+    ap.add_argument("--meta", choices=("f32", "f16"), default="f32",
+                    help="quantiser metadata format of the headline run: fp32 scale + int32 zero-point, or 16-bit scale + zero-point")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 1 GiB device-to-device copies (copy_probe_kernel), the known-size reference for HBM byte counters")
     args = ap.parse_args()
@@ -309,7 +311,8 @@ def main():
 
     w = si.WORKLOADS["vggt_stack"]
     n, H, d, L, NL = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens, w.n_layers
-    run = StackRun(torch, kvx, w, dev, 1, NL, 20, 102)
+    meta16 = args.meta == "f16"
+    run = StackRun(torch, kvx, w, dev, 1, NL, 20, 102, meta_format=kvx.KV_META_F16 if meta16 else kvx.KV_META_F32)
     if args.splits:
         run.h.set_option("attention_splits", args.splits)
     if args.no_overlap:
@@ -348,12 +351,13 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "vggt_stack: 24 layer caches per frame in one kv_step_batched, 16 heads x 64, 1041 tokens/frame, budget "
-                               "16384 tokens/layer, INT4 K per-channel g64 / INT4 V per-token g64, fp32 scale + int32 zero-point, steady state",
+                               "16384 tokens/layer, INT4 K per-channel g64 / INT4 V per-token g64, " +
+                               ("16-bit scale + zero-point" if meta16 else "fp32 scale + int32 zero-point") + ", steady state",
                    "keys_per_step": L + n, "layers": NL, "attention_splits": args.splits or "auto"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": attention_traffic("vggt_stack", "f32"),
-                     "kernel": "attn_kernel", "flops_per_launch": flops, "avg_launch_us": round(attn_s * 1e6, 2)},
-        "hbm_kernels": hbm_report(w, NL, us),
+                     "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": attention_traffic("vggt_stack", args.meta),
+                     "kernel": "attn16_kernel" if meta16 else "attn_kernel", "flops_per_launch": flops, "avg_launch_us": round(attn_s * 1e6, 2)},
+        "hbm_kernels": hbm_report(w, NL, us, 4 if meta16 else 8),
         "kernel_us": {k: round(v, 2) for k, v in us.items()},
         "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "live_per_frame_step": st["bytes_live_per_cache"] * NL,
                      "allocated": st["bytes_allocated"], "allocated_per_cache": st["bytes_allocated"] // NL,
@@ -361,7 +365,7 @@ def main():
                      "allocated_over_bf16_equivalent": round(st["bytes_allocated"] / NL / (2 * H * L * d * 2), 3)},
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = oracle_baseline(torch, run, fill + 3, 3)
+        res["cpu_baseline"] = oracle_baseline(torch, run, fill + 3, 3, meta16)
     else:
         res["cpu_baseline"] = None
     run.close()
