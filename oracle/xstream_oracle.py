@@ -21,7 +21,9 @@ Precision: attention is evaluated in fp64.  Everything that decides an integer
 (the importance scores that feed top-k, the quantiser's scale, zero-point and
 codes) is evaluated in fp32 with one rounding per arithmetic operation and a
 fixed order of additions, stated at each function, because the kept indices and
-the codes are compared bit-for-bit.
+the codes are compared bit-for-bit.  The paper gives no evaluation order for
+Eq. 5-6; the one fixed here for keys held as codes (importance_scores_codes)
+pulls the per-group factors q~ s and -z q~ s out of the per-token work.
 
 Readings of points the paper leaves open (each also listed in the design
 notes): attention runs before pruning; the current frame enters its own
@@ -274,13 +276,52 @@ def importance_scores(qt: np.ndarray, k_mid: np.ndarray) -> np.ndarray:
 
     Eq. 5-6 average the rows of Qbar Kbar^T; by linearity that is q~ . Kbar_j
     with q~ the row-mean of Qbar, and Kbar_j the head-mean key (Eq. 4).
-    Evaluated as: per head D[h, j] = tree_dot(q~, K~[h, j, :]); then add heads
+    Evaluated as: per head D[h, j] = tree_dot(q~, K[h, j, :]); then add heads
     0..H-1 in order and divide by H.
 
-    k_mid: fp32 [H, M, d] (the keys as stored: de-quantised codes).
+    k_mid: fp32 [H, M, d].  This is the form for keys held as fp32 values (the
+    pruning-only cache); keys held as codes go through importance_scores_codes.
     """
     H = k_mid.shape[0]
     D = tree_dot(qt, k_mid)                       # [H, M]
+    acc = D[0].copy()
+    for h in range(1, H):
+        acc = (acc + D[h]).astype(F32)
+    return (acc / F32(H)).astype(F32)
+
+
+def fma32(x: np.ndarray, y: np.ndarray, z: np.ndarray) -> np.ndarray:
+    """x * y + z with one rounding to fp32 (a fused multiply-add), for fp32 inputs.
+
+    Evaluated in fp64: the product of two fp32 values is exact there, and the sum is exact
+    whenever the two terms' exponents are within 20 of each other or one of them is zero,
+    which holds for every use below unless a zero-point exceeds 2^20 (such groups are
+    reported as range warnings; for them the last bit of a score may differ from a true
+    fused operation with probability around 2^-29 per term).
+    """
+    return (x.astype(np.float64) * y.astype(np.float64) + z.astype(np.float64)).astype(F32)
+
+
+def importance_scores_codes(qt: np.ndarray, codes: np.ndarray, s: np.ndarray, z: np.ndarray, grp: np.ndarray) -> np.ndarray:
+    """S_j of Eq. 6 for middle tokens held as codes, in fp32.
+
+    The same quantity as importance_scores (q~ . Kbar_j with the keys of Eq. 10), with the
+    per-group constants pulled out of the per-token work: per head, key group and channel
+    a = q~[c] * s[c] and b = -float(z[c]) * a (one rounding each); per token and channel
+    p[c] = fma(float(code[c]), a[c], b[c]) (one rounding); then the same stride-halving tree
+    over the channels, heads added 0..H-1 in order, divided by H.
+
+    codes: uint8 [H, M, d]; s fp32 and z int32 [H, G, d]; grp: int [M], key group of each token.
+    """
+    H = codes.shape[0]
+    a = (qt.astype(F32)[None, None, :] * s.astype(F32)).astype(F32)                  # [H, G, d]
+    b = ((-z.astype(F32)) * a).astype(F32)
+    p = fma32(codes.astype(F32), a[:, grp, :], b[:, grp, :])                          # [H, M, d]
+    m = p.shape[-1] // 2
+    while m >= 1:
+        p = (p[..., :m] + p[..., m:2 * m]).astype(F32)
+        m //= 2
+    D = p[..., 0]
     acc = D[0].copy()
     for h in range(1, H):
         acc = (acc + D[h]).astype(F32)
@@ -401,8 +442,12 @@ class OracleCache:
             n_first = min(n, T_old)          # tokens of the first frame
             n_current = n
             qt = pooled_query_mean(q, c.n_special, c.pool_group)
-            k_mid = k_all[:, n_first:T - n_current, :]
-            scores = importance_scores(qt, k_mid)
+            if c.quant:
+                # the middle tokens are all cached (the current frame is the last n_current positions)
+                pos = np.arange(n_first, T - n_current)
+                scores = importance_scores_codes(qt, self.Kc[:, pos, :], self.Ks, self.Kz, pos // c.k_group)
+            else:
+                scores = importance_scores(qt, k_all[:, n_first:T - n_current, :])
             keep = select_keep(scores, T, n_first, n_current, c.budget_tokens)
             self.last_keep = keep
             self.last_scores = scores

@@ -107,51 +107,82 @@ __global__ __launch_bounds__(1024) void pool_mean_kernel(const KvxBatch b) {
   if (tid < kHeadDim) reinterpret_cast<float*>(sc + g.sl.qt)[tid] = acc / (float)g.n_pooled;
 }
 
+// One row's codes as floats, channel by channel, through byte conversions (v_cvt_f32_ubyteN): 4-bit codes are
+// first spread into the bytes of two words per eight channels (even and odd channels), 2-bit codes into four.
+template <int K>
+__device__ __forceinline__ float byte_as_float(uint32_t w) {
+  float f;
+  if constexpr (K == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(f) : "v"(w));
+  else if constexpr (K == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(f) : "v"(w));
+  else if constexpr (K == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(f) : "v"(w));
+  else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(f) : "v"(w));
+  return f;
+}
+// f[0..7] = codes of channels 8 o .. 8 o + 7 of a row whose words are w
 template <int B>
-__device__ __forceinline__ int row_code(const uint32_t* w, int c) {
-  if constexpr (B == 4) return (int)((w[c >> 3] >> (4 * (c & 7))) & 0xFu);
-  if constexpr (B == 2) return (int)((w[c >> 4] >> (2 * (c & 15))) & 0x3u);
-  return (int)((w[c >> 2] >> (8 * (c & 3))) & 0xFFu);
+__device__ __forceinline__ void octet_as_floats(const uint32_t* w, int o, float (&f)[8]) {
+  if constexpr (B == 8) {
+    const uint32_t x = w[2 * o], y = w[2 * o + 1];
+    f[0] = byte_as_float<0>(x); f[1] = byte_as_float<1>(x); f[2] = byte_as_float<2>(x); f[3] = byte_as_float<3>(x);
+    f[4] = byte_as_float<0>(y); f[5] = byte_as_float<1>(y); f[6] = byte_as_float<2>(y); f[7] = byte_as_float<3>(y);
+  } else if constexpr (B == 4) {
+    const uint32_t x = w[o], ev = x & 0x0F0F0F0Fu, od = (x >> 4) & 0x0F0F0F0Fu;
+    f[0] = byte_as_float<0>(ev); f[2] = byte_as_float<1>(ev); f[4] = byte_as_float<2>(ev); f[6] = byte_as_float<3>(ev);
+    f[1] = byte_as_float<0>(od); f[3] = byte_as_float<1>(od); f[5] = byte_as_float<2>(od); f[7] = byte_as_float<3>(od);
+  } else {
+    const uint32_t x = (w[o >> 1] >> (16 * (o & 1))) & 0xFFFFu;          // eight 2-bit codes
+    const uint32_t t = x | (x << 12);                                     // codes 0..3 in bits 0..7, 4..7 again at bits 20..27
+    const uint32_t lo = t & 0x03000003u, m1 = (t >> 2) & 0x03000003u, m2 = (t >> 4) & 0x03000003u, m3 = (t >> 6) & 0x03000003u;
+    // byte 0 of each word holds code k, byte 3 holds code k + 4
+    f[0] = byte_as_float<0>(lo); f[4] = byte_as_float<3>(lo);
+    f[1] = byte_as_float<0>(m1); f[5] = byte_as_float<3>(m1);
+    f[2] = byte_as_float<0>(m2); f[6] = byte_as_float<3>(m2);
+    f[3] = byte_as_float<0>(m3); f[7] = byte_as_float<3>(m3);
+  }
 }
 
-// Per head and cached token: D[h, j] = q~ . K~[h, j, :] with K~ = s * (code - z) (Eq. 10),
-// p[c] = q~[c] * K~[c], then the stride-halving pairwise tree p[c] += p[c + m] for
-// m = 32, 16, ..., 1.  One thread holds one token's 64 channels; a block covers 256
-// consecutive cache positions of one head and stages their groups' (s, z) and q~ in LDS.
+// Per head and middle token: D[h, j] = sum over channels of q~[c] K~[h, j, c], K~ = s (code - z) (Eq. 10), evaluated
+// with the per-group factors pulled out of the per-token work: a = q~[c] * s[c] and b = -float(z[c]) * a once per
+// (head, key group, channel), p[c] = fma(float(code[c]), a[c], b[c]) per token, then the stride-halving pairwise tree
+// p[c] += p[c + m] for m = 32, 16, ..., 1.  One thread holds one token's 64 channels; a block covers 256 consecutive
+// cache positions of one head, starting behind the first frame (whose tokens are never scored), and stages a and b of
+// the key groups it touches in LDS.
+constexpr int kScoreGroupsMax = 256 / 32 + 1;
 template <int B>
 __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.z];
   if (!it.prune) return;
   const int h = blockIdx.y;
-  const int j0 = blockIdx.x * 256;
+  const int j0 = g.n + blockIdx.x * 256;
   if (j0 >= it.t_c) return;
   const uint8_t* half = cache_half(g, it.cache, it.cur);
   constexpr int kRowWords = 2 * B;                 // 64 channels * B bits / 32
-  __shared__ __attribute__((aligned(16))) float s_s[8][kHeadDim];
-  __shared__ __attribute__((aligned(16))) int32_t s_z[8][kHeadDim];
-  __shared__ __attribute__((aligned(16))) float s_q[kHeadDim];
+  __shared__ __attribute__((aligned(16))) float s_a[kScoreGroupsMax][kHeadDim];
+  __shared__ __attribute__((aligned(16))) float s_b[kScoreGroupsMax][kHeadDim];
 
   const int k_shift = g.k_group == 64 ? 6 : 5;      // groups of 64 or 32 tokens
-  const int groups_in_block = 256 >> k_shift;      // 4 or 8
   const int grp0 = j0 >> k_shift;
+  const int groups_in_block = ((min(j0 + 255, it.t_c - 1)) >> k_shift) - grp0 + 1;      // <= 5 or 9
+  const float* qt = reinterpret_cast<const float*>(cache_scratch(g, it.cache) + g.sl.qt);
   for (int i = threadIdx.x; i < groups_in_block * kHeadDim; i += 256) {
     const int gi = i >> 6, c = i & 63;
     const int grp = grp0 + gi;
-    if (grp < g.g_cap) {
-      if (g.meta16) {
-        // halfs: logit-domain scale a (s = a * fp32(1 / scale_log2)) and 1024 + z, channels of an octet in the order 0 4 1 5 2 6 3 7
-        const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + meta16_pos(c);
-        s_s[gi][c] = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(half + g.lay.k_scale)[moff]) * g.inv_scale_log2;
-        s_z[gi][c] = (int32_t)(float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(half + g.lay.k_zero)[moff]) - 1024;
-      } else {
-        const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + c;
-        s_s[gi][c] = reinterpret_cast<const float*>(half + g.lay.k_scale)[moff];
-        s_z[gi][c] = reinterpret_cast<const int32_t*>(half + g.lay.k_zero)[moff];
-      }
+    float sv, zf;
+    if (g.meta16) {
+      // halves: logit-domain scale a16 (s = a16 * fp32(1 / scale_log2)) and 1024 + z, channels of an octet in the order 0 4 1 5 2 6 3 7
+      const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + meta16_pos(c);
+      sv = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(half + g.lay.k_scale)[moff]) * g.inv_scale_log2;
+      zf = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(half + g.lay.k_zero)[moff]) - 1024.0f;
+    } else {
+      const int64_t moff = ((int64_t)h * g.g_cap + grp) * kHeadDim + c;
+      sv = reinterpret_cast<const float*>(half + g.lay.k_scale)[moff];
+      zf = (float)reinterpret_cast<const int32_t*>(half + g.lay.k_zero)[moff];
     }
+    const float a = qt[c] * sv;
+    s_a[gi][c] = a;
+    s_b[gi][c] = (-zf) * a;
   }
-  if (threadIdx.x < 64) s_q[threadIdx.x] = reinterpret_cast<const float*>(cache_scratch(g, it.cache) + g.sl.qt)[threadIdx.x];
   __syncthreads();
 
   const int j = j0 + threadIdx.x;
@@ -160,12 +191,22 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
   const uint32_t* src = reinterpret_cast<const uint32_t*>(half + g.lay.k_codes + ((int64_t)h * g.t_cap + j) * (8 * B));
 #pragma unroll
   for (int i = 0; i < kRowWords; ++i) w[i] = src[i];
-  const int gi = (j - j0) >> k_shift;
+  const int gi = (j >> k_shift) - grp0;
   float p[kHeadDim];
 #pragma unroll
-  for (int c = 0; c < kHeadDim; ++c) {
-    const float kd = s_s[gi][c] * (float)(row_code<B>(w, c) - s_z[gi][c]);
-    p[c] = s_q[c] * kd;
+  for (int o = 0; o < 8; ++o) {
+    float f[8];
+    octet_as_floats<B>(w, o, f);
+    const float4 a0 = *reinterpret_cast<const float4*>(&s_a[gi][8 * o]), a1 = *reinterpret_cast<const float4*>(&s_a[gi][8 * o + 4]);
+    const float4 b0 = *reinterpret_cast<const float4*>(&s_b[gi][8 * o]), b1 = *reinterpret_cast<const float4*>(&s_b[gi][8 * o + 4]);
+    p[8 * o + 0] = __builtin_fmaf(f[0], a0.x, b0.x);
+    p[8 * o + 1] = __builtin_fmaf(f[1], a0.y, b0.y);
+    p[8 * o + 2] = __builtin_fmaf(f[2], a0.z, b0.z);
+    p[8 * o + 3] = __builtin_fmaf(f[3], a0.w, b0.w);
+    p[8 * o + 4] = __builtin_fmaf(f[4], a1.x, b1.x);
+    p[8 * o + 5] = __builtin_fmaf(f[5], a1.y, b1.y);
+    p[8 * o + 6] = __builtin_fmaf(f[6], a1.z, b1.z);
+    p[8 * o + 7] = __builtin_fmaf(f[7], a1.w, b1.w);
   }
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) {
@@ -181,7 +222,7 @@ void launch_pool(const KvxBatch& b, hipStream_t st) {
 }
 
 void launch_score(const KvxBatch& b, int max_tc, hipStream_t st) {
-  dim3 grid((max_tc + 255) / 256, b.g.H, b.n_items);
+  dim3 grid((std::max(max_tc - b.g.n, 1) + 255) / 256, b.g.H, b.n_items);      // the middle tokens: behind the first frame
   switch (b.g.k_bits) {
     case 2: hipLaunchKernelGGL(score_dots_kernel<2>, grid, dim3(256), 0, st, b); break;
     case 4: hipLaunchKernelGGL(score_dots_kernel<4>, grid, dim3(256), 0, st, b); break;

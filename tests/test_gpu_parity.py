@@ -73,46 +73,6 @@ def test_vggt_layer_all_frames():
     pu.run_stream(si.WORKLOADS["vggt_layer"], 32, check_every=8)
 
 
-def test_vggt_stack_all_layers_batched_across_onset():
-    """Budget 16384: all 24 layer caches stepped by one kv_step_batched call per frame, the launch configuration the
-    benchmark's batched measurement times, 18 frames (pruning starts at the 16th).  Layers 0 and 23 run their own
-    inputs and are compared with the oracle; every other layer is fed the inputs of one of the two and must
-    reproduce that layer's outputs and cache bit for bit."""
-    import torch
-    from oracle import xstream_oracle as xo
-    w = si.WORKLOADS["vggt_stack"]
-    layers = [0, 23]
-    twin = {l: (0 if l % 2 == 0 else 23) for l in range(24)}
-    h = pu.make_handle(w, n_layers=24)
-    caches = {l: xo.OracleCache(pu.oracle_cfg(w)) for l in layers}
-    sig = {l: si.key_channel_scales(w, 0, l) for l in layers}
-    for t in range(18):
-        dev, ref = {}, {}
-        for l in layers:
-            q, k, v = si.frame_qkv(w, t, 0, l, sig[l])
-            ref[l] = caches[l].step(q, k, v)
-            dev[l] = tuple(pu.to_device(a, w) for a in (q, k, v))
-        outs = [torch.empty(dev[0][0].shape, dtype=torch.float32, device=dev[0][0].device) for _ in range(24)]
-        h.step_batched([(0, l, *dev[twin[l]], outs[l]) for l in range(24)])
-        torch.cuda.synchronize()
-        for l in layers:
-            e = pu.check_output(outs[l].cpu().numpy(), ref[l], f"stack layer {l} frame {t}")
-            if t >= 14:
-                pu.check_state(h.export(0, l), caches[l], f"stack layer {l} frame {t}")
-        for l in range(24):
-            assert torch.equal(outs[l], outs[twin[l]]), f"layer {l} frame {t}: output differs from layer {twin[l]}"
-        if t >= 15:
-            for l in (7, 12, 22):
-                a_, b_ = h.export(0, l), h.export(0, twin[l])
-                for name in ("ids", "k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "last_keep", "last_scores"):
-                    if a_[name] is None:
-                        assert b_[name] is None
-                    else:
-                        assert np.array_equal(a_[name].view(np.uint8), b_[name].view(np.uint8)), f"layer {l} frame {t}: {name}"
-        print(f"  vggt_stack frame {t}: len {caches[0].cache_len} err {e}", flush=True)
-    h.close()
-
-
 def test_vggt_hires_int2_keys_across_onset():
     """518x518 frames (1374 tokens), budget 24576, INT2 keys in groups of 32, INT4 values: 20 frames
     of one stream and layer (pruning starts at the 18th)."""

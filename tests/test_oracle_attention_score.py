@@ -196,3 +196,88 @@ def test_order_key_is_monotone():
     vals = np.array([-np.inf, -3.5, -1e-30, -0.0, 0.0, 1e-30, 2.0, np.inf], dtype=np.float32)
     keys = xo.order_key(vals).astype(np.int64)
     assert np.all(np.diff(keys) > 0)
+
+
+# ----------------------------------------------------------------------------- score over codes
+def _quantised_keys(rng, H, M, d, bits, G):
+    k = (rng.standard_normal((H, M, d)) * np.exp(rng.standard_normal((H, 1, d)))).astype(np.float32)
+    ng = -(-M // G)
+    codes = np.zeros((H, M, d), np.uint8)
+    s = np.zeros((H, ng, d), np.float32)
+    z = np.zeros((H, ng, d), np.int32)
+    for m in range(ng):
+        c_, s_, z_ = xo.quantize_k_group(k[:, m * G:(m + 1) * G, :], bits)
+        codes[:, m * G:(m + 1) * G, :], s[:, m], z[:, m] = c_, s_, z_
+    return codes, s, z, np.arange(M) // G
+
+
+@pytest.mark.parametrize("bits,G", [(4, 8), (2, 4), (8, 16)])
+def test_scores_over_codes_match_the_printed_equations(bits, G):
+    """The code form against Eq. 2-6 as printed (fp64, brute force) on the de-quantised keys."""
+    rng = np.random.default_rng(bits)
+    n, H, d, M, n_special, g = 21, 3, 8, 29, 5, 4
+    q = rng.standard_normal((n, H, d)).astype(np.float32)
+    codes, s, z, grp = _quantised_keys(rng, H, M, d, bits, G)
+    k_deq = xo.dequant(codes, s[:, grp, :], z[:, grp, :])
+    qt = xo.pooled_query_mean(q, n_special, g)
+    got = xo.importance_scores_codes(qt, codes, s, z, grp).astype(np.float64)
+    brute, _ = _brute_scores(q, k_deq, n_special, g)
+    assert np.abs(got - brute).max() < 1e-5 * np.abs(brute).max() + 1e-7
+    # and within the same band of the value form, whose kept set it must share away from near-ties
+    other = xo.importance_scores(qt, k_deq).astype(np.float64)
+    assert np.abs(got - other).max() < 1e-5 * np.abs(brute).max() + 1e-7
+
+
+def _round_fraction_to_f32(fr):
+    """Correctly rounded (nearest, ties to even) fp32 value of an exact rational, by integer arithmetic."""
+    from fractions import Fraction
+    if fr == 0:
+        return np.float32(0.0)
+    sign = -1 if fr < 0 else 1
+    fr = abs(fr)
+    e = 0
+    while fr >= 2 ** 24:
+        fr /= 2
+        e += 1
+    while fr < 2 ** 23:
+        fr *= 2
+        e -= 1
+    n, rem = divmod(fr.numerator, fr.denominator)
+    twice = 2 * rem
+    if twice > fr.denominator or (twice == fr.denominator and n % 2 == 1):
+        n += 1
+    return np.float32(sign * float(Fraction(n) * Fraction(2) ** e))
+
+
+def test_fused_multiply_add_is_a_single_rounding():
+    """fma32 against exact rational arithmetic rounded once, on code x scale + offset shaped operands
+    (including sums that land next to an fp32 tie)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(17)
+    code = rng.integers(0, 256, size=3000).astype(np.float32)
+    a = (rng.standard_normal(3000) * np.exp(rng.normal(0, 3, 3000))).astype(np.float32)
+    zf = rng.integers(-300, 300, size=3000).astype(np.float32)
+    b = (-zf * a).astype(np.float32)
+    got = xo.fma32(code, a, b)
+    for i in range(3000):
+        exact = Fraction(float(code[i])) * Fraction(float(a[i])) + Fraction(float(b[i]))
+        assert got[i] == _round_fraction_to_f32(exact), i
+    # a product that needs more than 24 bits, where rounding the product first would differ
+    x, y, zc = np.float32(3.0), np.float32(1 + 2.0 ** -23), np.float32(-3.0)
+    assert xo.fma32(x, y, zc) == np.float32(3 * 2.0 ** -23)
+    assert np.float32(np.float32(x * y) + zc) != np.float32(3 * 2.0 ** -23)
+
+
+def test_scores_over_codes_follow_the_stated_order():
+    """One head, one group, hand-sized: a = q~ s, b = -z a, p = fma(code, a, b), then the stride-halving tree."""
+    d = 4
+    qt = np.array([1.0, 2.0, 0.5, 1.0], np.float32)
+    s = np.array([[[0.5, 0.25, 2.0, 1.0]]], np.float32)
+    z = np.array([[[1, 0, 2, 3]]], np.int32)
+    codes = np.array([[[3, 4, 1, 3], [0, 0, 0, 0]]], np.uint8)
+    # a = [0.5, 0.5, 1, 1], b = [-0.5, 0, -2, -3]; token 0: p = [1, 2, -1, 0] -> (1 + -1) + (2 + 0) = 2; token 1: p = b -> -5.5
+    got = xo.importance_scores_codes(qt, codes, s, z, np.array([0, 0]))
+    assert got.tolist() == [2.0, -5.5]
+    # equals q~ . (s (code - z)) exactly here
+    kd = xo.dequant(codes, s[:, [0, 0], :], z[:, [0, 0], :])
+    assert xo.importance_scores(qt, kd).tolist() == [2.0, -5.5]
