@@ -131,7 +131,7 @@ __device__ __forceinline__ void octet_as_floats(const uint32_t* w, int o, float 
     f[1] = byte_as_float<0>(od); f[3] = byte_as_float<1>(od); f[5] = byte_as_float<2>(od); f[7] = byte_as_float<3>(od);
   } else {
     const uint32_t x = (w[o >> 1] >> (16 * (o & 1))) & 0xFFFFu;          // eight 2-bit codes
-    const uint32_t t = x | (x << 12);                                     // codes 0..3 in bits 0..7, 4..7 again at bits 20..27
+    const uint32_t t = x | (x << 16);                                     // codes 0..3 in bits 0..7, codes 4..7 in bits 24..31
     const uint32_t lo = t & 0x03000003u, m1 = (t >> 2) & 0x03000003u, m2 = (t >> 4) & 0x03000003u, m3 = (t >> 6) & 0x03000003u;
     // byte 0 of each word holds code k, byte 3 holds code k + 4
     f[0] = byte_as_float<0>(lo); f[4] = byte_as_float<3>(lo);
