@@ -26,8 +26,11 @@ Eq. 5-6; the one fixed here for keys held as codes (importance_scores_codes)
 pulls the per-group factors q~ s and -z q~ s out of the per-token work.
 
 Readings of points the paper leaves open (each also listed in the design
-notes): attention runs before pruning; the current frame enters its own
-attention at input precision; a short last patch group is averaged over its
+notes): attention runs before pruning and the current frame enters its own
+attention at input precision (the attend_after_prune switch takes the other
+order: update first, attend over codes only); a call may carry a chunk of
+several frames, attended with the frame-wise causal mask and appended as one
+block of current tokens; a short last patch group is averaged over its
 own size; ties in top-k keep the lower cache position and survivors stay in
 ascending position order; rounding is to nearest-even; the zero-point is not
 clamped (with 16-bit metadata, the meta16 switch, scales are rounded up to their
@@ -68,6 +71,8 @@ class OracleConfig:
     quant: bool = True               # False: keep fp32 K/V (pruning only)
     requant_v: bool = False          # True: re-quantise V every step (literal reading; diagnostic)
     meta16: bool = False             # True: 16-bit scales and zero-points (see quant_params_meta16_k / _v)
+    attend_after_prune: bool = False # True: the other reading of Fig. 2's order: append, prune, quantise, then attend
+                                     #       over the compressed cache (current frame in codes, exactly <= L_max keys)
 
 
 # --------------------------------------------------------------------------
@@ -231,7 +236,7 @@ def pooled_groups(n: int, n_special: int, g: int):
     return groups
 
 
-def pooled_query_mean(q: np.ndarray, n_special: int, g: int) -> np.ndarray:
+def pooled_query_mean(q: np.ndarray, n_special: int, g: int, n_frame: int = 0) -> np.ndarray:
     """q~[c] = mean over pooled rows of the head-mean pooled query (Eq. 2-3 and
     the row-mean of Eq. 6 pulled inside the product), in fp32.
 
@@ -239,10 +244,18 @@ def pooled_query_mean(q: np.ndarray, n_special: int, g: int) -> np.ndarray:
       per (head, pooled row): add the group's tokens in ascending order, divide by its size;
       per pooled row: add heads 0..H-1 in order, divide by H;
       add pooled rows in ascending order, divide by N_pooled.
+
+    n_frame: tokens per frame when q holds several frames one after the other (a chunk):
+    every frame is pooled by itself (its special tokens, then its patch groups) and the
+    rows of all frames are averaged together, in frame order.  0: q is one frame.
     """
     q = np.asarray(q, dtype=F32)
     n, H, d = q.shape
-    groups = pooled_groups(n, n_special, g)
+    if n_frame and n_frame != n:
+        assert n % n_frame == 0
+        groups = [(f * n_frame + a, f * n_frame + b) for f in range(n // n_frame) for (a, b) in pooled_groups(n_frame, n_special, g)]
+    else:
+        groups = pooled_groups(n, n_special, g)
     acc_rows = np.zeros(d, dtype=F32)
     for (a, b) in groups:
         acc_h = np.zeros(d, dtype=F32)
@@ -412,38 +425,55 @@ class OracleCache:
         z = np.repeat(self.Vz, c.v_group, axis=2)
         return dequant(self.Vc, s, z)
 
-    # -- one frame -------------------------------------------------------------------
+    # -- one frame, or a chunk of frames ----------------------------------------------
     def step(self, q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
+        """One call of the hot path.  q, k, v: [F n, H, d], F >= 1 consecutive frames.
+
+        Frame-wise causal attention (Sec. 3.1, Eq. 1): a query of the chunk's frame a sees the
+        cache as it was before the call and the chunk's frames 0..a at input precision.  The
+        cache is then updated once with the whole chunk as the current tokens: T_current = F n,
+        k = max(0, L_max - T_first - T_current), the pooled query of Eq. 2-3 taken over all F
+        frames.  With attend_after_prune the update comes first and attention runs over the
+        updated cache (one frame per call in that order).
+        """
         c = self.cfg
-        n, H, d = q.shape
-        assert (n, H, d) == (c.tokens_per_frame, c.n_heads, c.head_dim)
+        m, H, d = q.shape
+        n = c.tokens_per_frame
+        assert (H, d) == (c.n_heads, c.head_dim) and m >= n and m % n == 0
+        F = m // n
+        assert not (c.attend_after_prune and F > 1)
         q = np.asarray(q, dtype=F32)
-        k_new = np.ascontiguousarray(np.asarray(k, dtype=F32).transpose(1, 0, 2))   # [H, n, d]
+        k_new = np.ascontiguousarray(np.asarray(k, dtype=F32).transpose(1, 0, 2))   # [H, F n, d]
         v_new = np.ascontiguousarray(np.asarray(v, dtype=F32).transpose(1, 0, 2))
         scale = c.softmax_scale if c.softmax_scale != 0 else 1.0 / np.sqrt(d)
 
-        # Eq. 10 then Eq. 1: de-quantise the cache, attend over [cache; own frame].
+        # Eq. 10 then Eq. 1: de-quantise the cache, attend over [cache; the chunk up to the query's frame].
         k_old = self.stored_k()
         v_old = self.stored_v()
         k_all = np.concatenate([k_old, k_new], axis=1)
         v_all = np.concatenate([v_old, v_new], axis=1)
-        out = attention_fp64(q, k_all, v_all, scale)
+        T_old = self.cache_len
+        out = None
+        if not c.attend_after_prune:
+            out = np.empty((m, H, d), dtype=np.float64)
+            for a in range(F):
+                hi = T_old + (a + 1) * n
+                out[a * n:(a + 1) * n] = attention_fp64(q[a * n:(a + 1) * n], k_all[:, :hi, :], v_all[:, :hi, :], scale)
 
         # Append (Sec. 3.1, last sentence).
-        T_old = self.cache_len
-        ids_all = np.concatenate([self.ids, self.frames * n + np.arange(n, dtype=np.int32)]).astype(np.int32)
-        T = T_old + n
+        ids_all = np.concatenate([self.ids, self.frames * n + np.arange(m, dtype=np.int32)]).astype(np.int32)
+        T = T_old + m
         old_ids = self.ids
 
         # Prune when the cache length exceeds the budget (Sec. 3.2).
         self.last_keep = None
         self.last_scores = None
         if T > c.budget_tokens:
-            n_first = min(n, T_old)          # tokens of the first frame
-            n_current = n
-            qt = pooled_query_mean(q, c.n_special, c.pool_group)
+            n_first = min(n, T_old)          # tokens of the first frame (when it is not part of this very chunk)
+            n_current = m
+            qt = pooled_query_mean(q, c.n_special, c.pool_group, n)
             if c.quant:
-                # the middle tokens are all cached (the current frame is the last n_current positions)
+                # the middle tokens are all cached (the current tokens are the last n_current positions)
                 pos = np.arange(n_first, T - n_current)
                 scores = importance_scores_codes(qt, self.Kc[:, pos, :], self.Ks, self.Kz, pos // c.k_group)
             else:
@@ -462,7 +492,9 @@ class OracleCache:
             self.K = k_fin
             self.V = v_all[:, keep, :]
             self.ids = ids_new
-            self.frames += 1
+            self.frames += F
+            if c.attend_after_prune:
+                out = attention_fp64(q, self.K, self.V, scale)
             return out
 
         # Values: quantised once when their frame is appended, then carried (their
@@ -502,7 +534,10 @@ class OracleCache:
         self.Kc, self.Ks, self.Kz = Kc, Ks, Kz
         self.Vc, self.Vs, self.Vz = Vc, Vs, Vz
         self.ids = ids_new
-        self.frames += 1
+        self.frames += F
+        if c.attend_after_prune:
+            # Eq. 1 over the compressed cache: every key, the current frame's included, is a de-quantised code
+            out = attention_fp64(q, self.stored_k(), self.stored_v(), scale)
         return out
 
 

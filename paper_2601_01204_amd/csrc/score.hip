@@ -161,6 +161,15 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
   __shared__ __attribute__((aligned(16))) float s_a[kScoreGroupsMax][kHeadDim];
   __shared__ __attribute__((aligned(16))) float s_b[kScoreGroupsMax][kHeadDim];
 
+  // the token's code row is requested first, so that its latency runs beside the staging of the group factors
+  const int j = j0 + threadIdx.x;
+  uint32_t w[kRowWords];
+  {
+    const int jl = min(j, it.t_c - 1);
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(half + g.lay.k_codes + ((int64_t)h * g.t_cap + jl) * (8 * B));
+#pragma unroll
+    for (int i = 0; i < kRowWords; ++i) w[i] = src[i];
+  }
   const int k_shift = g.k_group == 64 ? 6 : 5;      // groups of 64 or 32 tokens
   const int grp0 = j0 >> k_shift;
   const int groups_in_block = ((min(j0 + 255, it.t_c - 1)) >> k_shift) - grp0 + 1;      // <= 5 or 9
@@ -185,12 +194,7 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
   }
   __syncthreads();
 
-  const int j = j0 + threadIdx.x;
   if (j >= it.t_c) return;
-  uint32_t w[kRowWords];
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(half + g.lay.k_codes + ((int64_t)h * g.t_cap + j) * (8 * B));
-#pragma unroll
-  for (int i = 0; i < kRowWords; ++i) w[i] = src[i];
   const int gi = (j >> k_shift) - grp0;
   float p[kHeadDim];
 #pragma unroll
