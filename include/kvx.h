@@ -58,6 +58,14 @@ enum kv_meta_format {
                     /* >= 65504 are outside its domain.                                                    */
 };
 
+enum kv_order {
+  KV_ATTEND_THEN_PRUNE = 0, /* Eq. 1 over [cache before the step ; the new frames at input precision], then the */
+                            /* cache update (Sec. 3.1: "after attention computation ... appended")              */
+  KV_PRUNE_THEN_ATTEND = 1  /* the other reading of Fig. 2's order: append, score, prune and quantise first,    */
+                            /* then Eq. 1 over the compressed cache (at most L_max keys, the current frame in   */
+                            /* codes like every other token).  One frame per call.                              */
+};
+
 enum kv_mode {
   KV_COMPRESSED = 0,        /* pruned + quantised cache (the paper's method)                */
   KV_UNCOMPRESSED_BF16 = 1  /* baseline: bf16 cache that grows by n tokens per frame,       */
@@ -84,6 +92,9 @@ typedef struct kv_config {
   int32_t max_frames;       /* KV_UNCOMPRESSED_BF16 only: frames the cache is sized for        */
   float softmax_scale;      /* 0 -> 1/sqrt(head_dim)                                           */
   int32_t meta_format;      /* kv_meta_format of the quantiser's scales and zero-points        */
+  int32_t max_frames_per_step; /* most frames one kv_step_frames call may carry (0 or 1: one); */
+                            /* budget_tokens must be >= (1 + max_frames_per_step) * tokens_per_frame */
+  int32_t order;            /* kv_order                                                        */
 } kv_config;
 
 typedef struct kv_handle kv_handle;
@@ -158,6 +169,18 @@ int kv_init(const kv_config* cfg, kv_handle** out);
  * validation precedes the first launch, so a failed call leaves the cache unchanged. */
 int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v,
             int64_t tok_stride, int64_t head_stride, void* out, void* hip_stream);
+
+/* A chunk of n_frames consecutive frames of one stream in one call (1 <= n_frames <= max_frames_per_step).
+ * q, k, v, out: device, [n_frames * n, H, d], frame after frame, strides as in kv_step.  Attention is the
+ * frame-wise causal one of Sec. 3.1 Eq. 1: a query of the chunk's frame a sees the cache as it was before
+ * the call and the chunk's frames 0..a at input precision, nothing of the frames after its own.  The cache is
+ * then updated once with the whole chunk as the current tokens of Sec. 3.2: T_current = n_frames * n,
+ * k = L_max - T_first - T_current, the pooled query of Eq. 2-3 taken over the rows of all the chunk's frames;
+ * the chunk's keys and values are quantised by Eq. 7-9 as in kv_step.  n_frames = 1 is kv_step.
+ * KV_E_RANGE for n_frames outside [1, max_frames_per_step]; KV_E_INVAL with KV_PRUNE_THEN_ATTEND and
+ * n_frames > 1. */
+int kv_step_frames(kv_handle* h, int32_t stream, int32_t layer, int32_t n_frames, const void* q, const void* k,
+                   const void* v, int64_t tok_stride, int64_t head_stride, void* out, void* hip_stream);
 
 /* kv_step for callers that cannot allocate device memory or let a library do so around the call:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same

@@ -9,6 +9,7 @@ import numpy as np
 KV_BF16, KV_F32 = 0, 1
 KV_COMPRESSED, KV_UNCOMPRESSED_BF16 = 0, 1
 KV_META_F32, KV_META_F16 = 0, 1
+KV_ATTEND_THEN_PRUNE, KV_PRUNE_THEN_ATTEND = 0, 1
 KERNEL_NAMES = ["attention", "combine", "pool", "score", "select", "rebuild_k", "rebuild_v"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -22,7 +23,7 @@ class KvConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_streams", "n_layers", "n_heads", "head_dim", "tokens_per_frame", "n_special", "pool_group",
         "budget_tokens", "k_bits", "k_group", "v_bits", "v_group", "in_dtype", "out_dtype", "mode", "max_frames")] + [
-        ("softmax_scale", C.c_float), ("meta_format", C.c_int32)]
+        ("softmax_scale", C.c_float), ("meta_format", C.c_int32), ("max_frames_per_step", C.c_int32), ("order", C.c_int32)]
 
 
 class KvStepItem(C.Structure):
@@ -69,6 +70,7 @@ def load_library():
     P = C.c_void_p
     lib.kv_init.argtypes = [C.POINTER(KvConfig), C.POINTER(P)]
     lib.kv_step.argtypes = [P, C.c_int32, C.c_int32, P, P, P, C.c_int64, C.c_int64, P, P]
+    lib.kv_step_frames.argtypes = [P, C.c_int32, C.c_int32, C.c_int32, P, P, P, C.c_int64, C.c_int64, P, P]
     lib.kv_step_static.argtypes = [P, C.c_int32, C.c_int32, P, P, P, C.c_int64, C.c_int64, P, P]
     lib.kv_step_batched.argtypes = [P, C.c_int32, C.POINTER(KvStepItem), C.c_int64, C.c_int64, P]
     lib.kv_stats.argtypes = [P, C.POINTER(KvStats)]
@@ -84,7 +86,7 @@ def load_library():
     lib.kv_set_option.argtypes = [P, C.c_char_p, C.c_int64]
     lib.kv_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, P, C.POINTER(C.c_double)]
     lib.kv_probe_copy.argtypes = [C.c_int64, C.c_int32, P, C.POINTER(C.c_double)]
-    for name in ("kv_init", "kv_step", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_timing",
+    for name in ("kv_init", "kv_step", "kv_step_frames", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_timing",
                  "kv_read_timing", "kv_set_option", "kv_probe_mfma_bf16", "kv_probe_copy", "kv_import"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -117,7 +119,7 @@ class KvHandle:
         c = KvConfig()
         defaults = dict(n_streams=1, n_layers=1, head_dim=64, pool_group=16, k_bits=4, k_group=64, v_bits=4, v_group=64,
                         in_dtype=KV_BF16, out_dtype=None, mode=KV_COMPRESSED, max_frames=0, softmax_scale=0.0, budget_tokens=0,
-                        meta_format=KV_META_F32)
+                        meta_format=KV_META_F32, max_frames_per_step=1, order=KV_ATTEND_THEN_PRUNE)
         defaults.update(cfg)
         if defaults["out_dtype"] is None:
             defaults["out_dtype"] = defaults["in_dtype"]
@@ -145,6 +147,15 @@ class KvHandle:
         assert self._strides(out) == (ts, hs)
         self._check(self.lib.kv_step(self._h, stream, layer, q.data_ptr(), k.data_ptr(), v.data_ptr(), ts, hs,
                                      out.data_ptr(), hip_stream))
+
+    def step_frames(self, n_frames: int, q, k, v, out, stream: int = 0, layer: int = 0, hip_stream: int = 0):
+        """kv_step_frames: q, k, v, out hold n_frames consecutive frames, [n_frames * n, H, d]."""
+        ts, hs = self._strides(q)
+        for t in (k, v):
+            assert self._strides(t) == (ts, hs) and t.dtype == q.dtype
+        assert self._strides(out) == (ts, hs)
+        self._check(self.lib.kv_step_frames(self._h, stream, layer, n_frames, q.data_ptr(), k.data_ptr(), v.data_ptr(), ts, hs,
+                                            out.data_ptr(), hip_stream))
 
     def step_static(self, q, k, v, out, stream: int = 0, layer: int = 0, hip_stream: int = 0):
         """kv_step_static: kv_step with the attention partials in the library's static device array."""

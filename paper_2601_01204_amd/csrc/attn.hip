@@ -175,10 +175,10 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   constexpr int kQSets = F32IN ? 2 : 1;                   // bf16 queries: one fragment set; fp32: hi and lo
   __shared__ uint4 lds_q[kAttnMaxWaves * kQSets * 4 * 64];   // waves x sets x 4 channel steps x 64 lanes
 
-  const int n = g.n;
+  const int n = g.n_new;                                  // query rows = the call's own keys: one frame, or a chunk of frames
   const int t_c = it.t_c;
   const int ntc = (t_c + kTileK - 1) / kTileK;            // cache tiles
-  const int nto = (n + kTileK - 1) / kTileK;              // own-frame tiles
+  const int nto = g.own_tiles ? (n + kTileK - 1) / kTileK : 0;   // tiles of the call's own keys (none when they are in the cache already)
   const int nt = ntc + nto;
   // contiguous, near-equal tile ranges per split
   const int tile_begin = (int)(((int64_t)nt * split) / g.n_splits);
@@ -192,6 +192,11 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   constexpr int NB = 1;
   const int row0 = (qt * g.q_blocks + wave) * 32;
   const int nblk = (wave < g.q_blocks && row0 < n) ? 1 : 0;
+  // Frame-wise causal mask inside the call's own keys (Sec. 3.1): a query of frame a sees own keys 0 .. (a + 1) n_frame - 1.
+  // own_limit: that count for this lane's query; own_limit_wave: the largest over the wave's rows (uniform).
+  const int own_limit = (min(row0 + l32, n - 1) / g.n + 1) * g.n;
+  const int own_limit_wave = (min(row0 + 31, n - 1) / g.n + 1) * g.n;
+  bool started = false;                                   // this wave has computed a tile (the first one sets m)
 
   // ---- this wave's query fragments (B operand of S^T = K Q^T) ---------------------
   // They live in a private LDS region of the wave, one 16-byte entry per lane and
@@ -469,10 +474,10 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
     pin_qk_steps<NB, F32IN, kAhead>(std::make_integer_sequence<int, 8>{});
     __builtin_amdgcn_s_setprio(0);
 
-    int valid;
-    if (t < ntc) valid = min(kTileK, t_c - t * kTileK); else valid = min(kTileK, n - (t - ntc) * kTileK);
-    // keys past `valid` (ragged last tile) drop out
-    if (valid < kTileK) {
+    // keys this lane's query may see in the tile: a cache tile's valid rows (ragged last tile), or the own keys up
+    // to the end of the query's frame (frame-wise causal mask; also covers the ragged end of the call's rows)
+    const int valid = (t < ntc) ? t_c - t * kTileK : own_limit - (t - ntc) * kTileK;
+    if (__any(valid < kTileK)) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -534,7 +539,8 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
 #pragma unroll
         for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s[0][nb][r]), s[1][nb][r]);
         const float mq = fmaxf(a, __shfl_xor(a, 32));                // both halves of a query agree
-        const float delta = (first || mq > kRescaleGap) ? mq : 0.f;
+        // a query that sees none of the tile's keys (all masked) keeps its reference
+        const float delta = ((first && mq > 0.5f * kNegBig) || mq > kRescaleGap) ? mq : 0.f;
         const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated before the first tile
         m_ref[nb] += delta;
         l_run[nb] *= alpha;
@@ -568,8 +574,12 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
     sched_group<0x008, 6 * NB>();
     __builtin_amdgcn_s_setprio(0);
   };
+  // a tile of own keys that lies wholly behind the frames of this wave's queries is skipped (wave-uniform)
   auto run_compute = [&](int t, int buf) __attribute__((always_inline)) {
-    if (nblk) compute(t, buf, buf, t == tile_begin);
+    if (nblk && !(t >= ntc && (t - ntc) * kTileK >= own_limit_wave)) {
+      compute(t, buf, buf, !started);
+      started = true;
+    }
   };
 
   // ---- tile loop --------------------------------------------------------------------
@@ -616,7 +626,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
   }
 
   // ---- epilogue -------------------------------------------------------------------
-  if (tile_begin >= tile_end) m_ref[0] = kNegBig;     // an empty key range weighs nothing in the merge
+  if (!started) m_ref[0] = kNegBig;     // an empty (or wholly masked) key range weighs nothing in the merge
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int qi = (nb < nblk) ? row0 + nb * 32 + l32 : n;
@@ -651,7 +661,8 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn_kernel(const KvxBatch
           *reinterpret_cast<float4*>(po + c) =
               make_float4(o[cb][nb][4 * r4 + 0], o[cb][nb][4 * r4 + 1], o[cb][nb][4 * r4 + 2], o[cb][nb][4 * r4 + 3]);
         }
-      if (hf == 0) *reinterpret_cast<float2*>(g.part_ml + row * 2) = make_float2(m_ref[nb], l_tot);
+      // a query that saw no key in this range (all masked) has l = 0: its reference must not raise the merge's maximum
+      if (hf == 0) *reinterpret_cast<float2*>(g.part_ml + row * 2) = make_float2(l_tot > 0.f ? m_ref[nb] : kNegBig, l_tot);
     }
   }
 }
@@ -663,7 +674,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const KvxBatch b) {
   const int h = blockIdx.y;
   const int qi = blockIdx.x * 16 + (threadIdx.x >> 4);
   const int c = (threadIdx.x & 15) * 4;
-  if (qi >= g.n) return;
+  if (qi >= g.n_new) return;
   // all partials are requested before any is used
   const int64_t row0 = ((int64_t)blockIdx.z * g.n_splits * g.H + h) * g.n_pad + qi;
   const int64_t row_step = (int64_t)g.H * g.n_pad;
@@ -726,7 +737,7 @@ void launch_attention(const KvxBatch& b, int /*max_tiles*/, hipStream_t st, hipE
 void launch_combine(const KvxBatch& b, hipStream_t st) {
   const Geometry& g = b.g;
   if (g.n_splits <= 1) return;
-  dim3 grid((g.n + 15) / 16, g.H, b.n_items);
+  dim3 grid((g.n_new + 15) / 16, g.H, b.n_items);
   hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, st, b);
 }
 

@@ -148,10 +148,10 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileElems];
   __shared__ uint4 lds_q[kAttnMaxWaves * 4 * 64];          // waves x 4 channel steps x 64 lanes
 
-  const int n = g.n;
+  const int n = g.n_new;                                  // query rows = the call's own keys: one frame, or a chunk of frames
   const int t_c = it.t_c;
   const int ntc = (t_c + kTileK - 1) / kTileK;            // cache tiles
-  const int nto = (n + kTileK - 1) / kTileK;              // own-frame tiles
+  const int nto = g.own_tiles ? (n + kTileK - 1) / kTileK : 0;   // tiles of the call's own keys (none when they are in the cache already)
   const int nt = ntc + nto;
   const int tile_begin = (int)(((int64_t)nt * split) / g.n_splits);
   const int tile_end = (int)(((int64_t)nt * (split + 1)) / g.n_splits);
@@ -160,6 +160,11 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
   const float sc = g.scale_log2;
   const int row0 = (qt * g.q_blocks + wave) * 32;
   const int nblk = (wave < g.q_blocks && row0 < n) ? 1 : 0;
+  // Frame-wise causal mask inside the call's own keys (Sec. 3.1): a query of frame a sees own keys 0 .. (a + 1) n_frame - 1.
+  // own_limit: that count for this lane's query; own_limit_wave: the largest over the wave's rows (uniform).
+  const int own_limit = (min(row0 + l32, n - 1) / g.n + 1) * g.n;
+  const int own_limit_wave = (min(row0 + 31, n - 1) / g.n + 1) * g.n;
+  bool started = false;                                   // this wave has computed a tile (the first one sets m)
 
   // ---- this wave's query fragments (B operand of S^T = K Q^T), halves, octets permuted ----
   uint4* qbase = lds_q + (wave * 4) * 64 + lane;
@@ -350,9 +355,10 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
         for (int r = 0; r < 16; ++r) s[mb][r] = __builtin_fmaf(s[mb][r], sc, nm);
     }
 
-    int valid;
-    if (t < ntc) valid = min(kTileK, t_c - t * kTileK); else valid = min(kTileK, n - (t - ntc) * kTileK);
-    if (valid < kTileK) {
+    // keys this lane's query may see in the tile: a cache tile's valid rows (ragged last tile), or the own keys up
+    // to the end of the query's frame (frame-wise causal mask; also covers the ragged end of the call's rows)
+    const int valid = (t < ntc) ? t_c - t * kTileK : own_limit - (t - ntc) * kTileK;
+    if (__any(valid < kTileK)) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -398,7 +404,8 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
 #pragma unroll
       for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s[0][r]), s[1][r]);
       const float mq = fmaxf(a, __shfl_xor(a, 32));                // both halves of a query agree
-      const float delta = (first || mq > kRescaleGap) ? mq : 0.f;
+      // a query that sees none of the tile's keys (all masked) keeps its reference
+      const float delta = ((first && mq > 0.5f * kNegBig) || mq > kRescaleGap) ? mq : 0.f;
       const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated before the first tile
       m_ref += delta;
       l_run *= alpha;
@@ -428,8 +435,12 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
     sched_group<0x008, 6>();
     __builtin_amdgcn_s_setprio(0);
   };
+  // a tile of own keys that lies wholly behind the frames of this wave's queries is skipped (wave-uniform)
   auto run_compute = [&](int t, int buf) __attribute__((always_inline)) {
-    if (nblk) compute(t, buf, buf, t == tile_begin);
+    if (nblk && !(t >= ntc && (t - ntc) * kTileK >= own_limit_wave)) {
+      compute(t, buf, buf, !started);
+      started = true;
+    }
   };
 
   // ---- tile loop --------------------------------------------------------------------
@@ -476,7 +487,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
   }
 
   // ---- epilogue -------------------------------------------------------------------
-  if (tile_begin >= tile_end) m_ref = kNegBig;     // an empty key range weighs nothing in the merge
+  if (!started) m_ref = kNegBig;     // an empty (or wholly masked) key range weighs nothing in the merge
   const int qi = nblk ? row0 + l32 : n;
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (g.n_splits == 1) {
@@ -508,7 +519,8 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
         const int c = cb * 32 + 8 * r4 + 4 * hf;
         *reinterpret_cast<float4*>(po + c) = make_float4(o[cb][4 * r4 + 0], o[cb][4 * r4 + 1], o[cb][4 * r4 + 2], o[cb][4 * r4 + 3]);
       }
-    if (hf == 0) *reinterpret_cast<float2*>(g.part_ml + row * 2) = make_float2(m_ref, l_tot);
+    // a query that saw no key in this range (all masked) has l = 0: its reference must not raise the merge's maximum
+    if (hf == 0) *reinterpret_cast<float2*>(g.part_ml + row * 2) = make_float2(l_tot > 0.f ? m_ref : kNegBig, l_tot);
   }
 }
 

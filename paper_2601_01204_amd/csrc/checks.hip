@@ -11,7 +11,7 @@ __global__ __launch_bounds__(256) void check_finite_kernel(const KvxBatch b) {
   const void* src = blockIdx.y == 0 ? it.q : (blockIdx.y == 1 ? it.k : it.v);
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;      // 8 channels of one (token, head) row
   const int64_t row = idx >> 3;
-  if (row >= (int64_t)g.n * g.H) return;
+  if (row >= (int64_t)g.n_new * g.H) return;
   const int tok = (int)(row / g.H), h = (int)(row % g.H), c0 = (int)(idx & 7) * 8;
   const int64_t off = (int64_t)tok * g.tok_stride + (int64_t)h * g.head_stride + c0;
   bool bad = false;
@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void check_finite_kernel(const KvxBatch b) {
 }
 
 void launch_check_finite(const KvxBatch& b, hipStream_t st) {
-  const int64_t lanes = (int64_t)b.g.n * b.g.H * 8;
+  const int64_t lanes = (int64_t)b.g.n_new * b.g.H * 8;
   hipLaunchKernelGGL(check_finite_kernel, dim3((unsigned)((lanes + 255) / 256), 3, b.n_items), dim3(256), 0, st, b);
 }
 

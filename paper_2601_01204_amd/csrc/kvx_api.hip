@@ -120,6 +120,8 @@ struct kv_handle {
   // attention launches of the same step (both only read the current cache half)
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  int32_t f_max = 1;          // most frames per call
+  int32_t n_pad_max = 0;      // padded query rows of the largest call (sizes the partial-result buffers)
   int32_t overlap = 1;
   int32_t debug_checks = 0;
   std::string err;
@@ -146,6 +148,17 @@ int fail(kv_handle* h, int code, const char* fmt, ...) {
 
 bool is_bits(int b) { return b == 2 || b == 4 || b == 8; }
 
+// Query tiling of a call that brings `rows` query rows: an attention workgroup holds up to 12 waves, one 32-row
+// query block each; the blocks are spread evenly over the fewest workgroups.
+void set_query_tiling(Geometry& g, int rows) {
+  const int nblocks = (rows + 31) / 32;
+  const int tile_blocks = 12;
+  g.n_new = rows;
+  g.n_qtiles = (nblocks + tile_blocks - 1) / tile_blocks;
+  g.q_blocks = (nblocks + g.n_qtiles - 1) / g.n_qtiles;
+  g.n_pad = g.n_qtiles * g.q_blocks * 32;
+}
+
 int validate(const kv_config* c) {
   if (!c) return fail(nullptr, KV_E_INVAL, "kv_init: cfg is NULL");
   if (c->n_streams < 1 || c->n_layers < 1) return fail(nullptr, KV_E_INVAL, "kv_init: n_streams and n_layers must be >= 1");
@@ -164,9 +177,13 @@ int validate(const kv_config* c) {
     if (c->k_bits != 2 && c->k_bits != 4) return fail(nullptr, KV_E_INVAL, "kv_init: KV_META_F16 needs k_bits of 2 or 4 (the key products are exact in half precision up to 4-bit codes)");
     if (c->in_dtype != KV_BF16) return fail(nullptr, KV_E_INVAL, "kv_init: KV_META_F16 needs in_dtype KV_BF16");
   }
+  if (c->order != KV_ATTEND_THEN_PRUNE && c->order != KV_PRUNE_THEN_ATTEND) return fail(nullptr, KV_E_INVAL, "kv_init: order must be KV_ATTEND_THEN_PRUNE or KV_PRUNE_THEN_ATTEND");
+  if (c->max_frames_per_step < 0 || c->max_frames_per_step > 64) return fail(nullptr, KV_E_INVAL, "kv_init: max_frames_per_step must be in [0, 64]");
+  if (c->order == KV_PRUNE_THEN_ATTEND && (c->mode != KV_COMPRESSED || c->max_frames_per_step > 1))
+    return fail(nullptr, KV_E_INVAL, "kv_init: KV_PRUNE_THEN_ATTEND applies to the compressed cache with one frame per call");
   if (c->mode == KV_COMPRESSED) {
-    if ((int64_t)c->budget_tokens < 2 * (int64_t)c->tokens_per_frame)
-      return fail(nullptr, KV_E_INVAL, "kv_init: budget_tokens must be >= 2 * tokens_per_frame (first and current frame are always kept)");
+    if ((int64_t)c->budget_tokens < (1 + (int64_t)std::max(1, c->max_frames_per_step)) * (int64_t)c->tokens_per_frame)
+      return fail(nullptr, KV_E_INVAL, "kv_init: budget_tokens must be >= (1 + max_frames_per_step) * tokens_per_frame (the first frame and the current frames are always kept)");
     if (c->budget_tokens > 32768) return fail(nullptr, KV_E_RANGE, "kv_init: budget_tokens above 32768 is not supported");
     if (!is_bits(c->k_bits) || !is_bits(c->v_bits)) return fail(nullptr, KV_E_INVAL, "kv_init: k_bits and v_bits must be 2, 4 or 8");
     if (c->k_group != 32 && c->k_group != 64) return fail(nullptr, KV_E_INVAL, "kv_init: k_group must be 32 or 64");
@@ -185,8 +202,7 @@ int validate(const kv_config* c) {
 // is rounds x (tiles per workgroup + a fixed per-workgroup cost of about three tiles for the
 // first loads and the partial-result store), and the split count with the smallest
 // estimate wins (fewer splits on ties: less merge traffic).
-int pick_splits(const kv_handle* h, int n_items, int min_tiles) {
-  const Geometry& g = h->geo;
+int pick_splits(const kv_handle* h, const Geometry& g, int n_items, int min_tiles) {
   int s;
   if (h->splits_override > 0) {
     s = h->splits_override;
@@ -279,14 +295,17 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   g.out_f32 = c.out_dtype == KV_F32;
   g.uncompressed = unc;
   g.meta16 = c.meta_format == KV_META_F16;
-  {
-    // an attention workgroup holds up to 12 waves, one 32-row query block each
-    const int nblocks = (g.n + 31) / 32;
-    const int tile_blocks = 12;
-    g.n_qtiles = (nblocks + tile_blocks - 1) / tile_blocks;
-    g.q_blocks = (nblocks + g.n_qtiles - 1) / g.n_qtiles;
-    g.n_pad = g.n_qtiles * g.q_blocks * 32;
+  h->f_max = std::max(1, c.max_frames_per_step);
+  g.own_tiles = 1;
+  // buffers are sized for the largest call; n_pad only grows with the row count
+  int n_pad_max = 0;
+  for (int f = 1; f <= h->f_max; ++f) {
+    set_query_tiling(g, f * g.n);
+    n_pad_max = std::max(n_pad_max, g.n_pad);
   }
+  int qtiles_one = 0;
+  set_query_tiling(g, g.n);
+  qtiles_one = g.n_qtiles;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / std::sqrt((float)kHeadDim);
   g.scale_log2 = scale * 1.4426950408889634f;
   g.inv_scale_log2 = 1.0f / g.scale_log2;
@@ -307,7 +326,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
 
   ScratchLayout& S = g.sl;
   off = 0;
-  S.qbar = off;   off = align_up(off + (int64_t)g.n_pooled * kHeadDim * 4, 256);
+  S.qbar = off;   off = align_up(off + (int64_t)g.n_pooled * h->f_max * kHeadDim * 4, 256);
   S.qt = off;     off = align_up(off + kHeadDim * 4, 256);
   S.dots = off;   off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * 4), 256);
   S.scores = off; off = align_up(off + (unc ? 0 : (int64_t)g.t_cap * 4), 256);
@@ -341,15 +360,16 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   h->slots_cap = 0;
   for (int items = 1; items <= std::min<int64_t>(kMaxItems, n_caches); ++items) {
     // the most splits pick_splits can choose for this many items when it aims at every compute unit
-    const int64_t base = (int64_t)items * g.H * g.n_qtiles;
+    const int64_t base = (int64_t)items * g.H * qtiles_one;      // fewest workgroup columns a call can have
     const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, 2 * (int64_t)cus / base));
     h->slots_cap = std::max(h->slots_cap, items * cap);
   }
   h->slots_cap = std::max(h->slots_cap, (int32_t)kMaxSplits);
   h->bytes_arena = n_caches * L.cache_bytes;
   h->bytes_scratch = n_caches * S.bytes;
-  const int64_t part_o_bytes = (int64_t)h->slots_cap * g.H * g.n_pad * kHeadDim * 4;
-  const int64_t part_ml_bytes = (int64_t)h->slots_cap * g.H * g.n_pad * 2 * 4;
+  h->n_pad_max = n_pad_max;
+  const int64_t part_o_bytes = (int64_t)h->slots_cap * g.H * n_pad_max * kHeadDim * 4;
+  const int64_t part_ml_bytes = (int64_t)h->slots_cap * g.H * n_pad_max * 2 * 4;
   h->bytes_part = part_o_bytes + part_ml_bytes;
 
   hipError_t e1 = hipMalloc((void**)&h->arena, (size_t)h->bytes_arena);
@@ -390,11 +410,15 @@ namespace {
 // One set of launches per group of up to kMaxItems caches.  part_o / part_ml: where the attention
 // kernel's key-range splits leave their partial results, room for slots_cap (cache, split) pairs.
 // with_timing = false: no event is created or recorded by this call.
-int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride, int64_t head_stride, void* hip_stream,
-              float* part_o, float* part_ml, int32_t slots_cap, bool with_timing) {
+int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t n_frames, int64_t tok_stride, int64_t head_stride,
+              void* hip_stream, float* part_o, float* part_ml, int32_t slots_cap, bool with_timing) {
   if (n_items < 1 || !items) return fail(h, KV_E_INVAL, "kv_step: no items");
   const kv_config& c = h->cfg;
-  const Geometry& g0 = h->geo;
+  if (n_frames < 1 || n_frames > h->f_max) return fail(h, KV_E_RANGE, "kv_step: %d frames in one call, the handle takes 1..%d (max_frames_per_step)", n_frames, h->f_max);
+  Geometry g0 = h->geo;
+  set_query_tiling(g0, n_frames * g0.n);
+  const int n_new = g0.n_new;
+  const bool update_first = c.order == KV_PRUNE_THEN_ATTEND;
   const int64_t elt = g0.in_f32 ? 4 : 2;
   if (head_stride < kHeadDim || tok_stride < kHeadDim) return fail(h, KV_E_INVAL, "kv_step: strides must be >= head_dim");
   const int64_t oelt = g0.out_f32 ? 4 : 2;
@@ -411,8 +435,8 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t 
     const size_t ci = (size_t)it.stream * c.n_layers + it.layer;
     if (h->seen_in_call[ci] == call) return fail(h, KV_E_INVAL, "kv_step: cache (stream %d, layer %d) appears twice in one batch", it.stream, it.layer);
     h->seen_in_call[ci] = call;
-    if (g0.uncompressed && h->caches[ci].frames >= c.max_frames)
-      return fail(h, KV_E_STATE, "kv_step: cache (stream %d, layer %d) already holds max_frames frames", it.stream, it.layer);
+    if (g0.uncompressed && h->caches[ci].frames + n_frames > c.max_frames)
+      return fail(h, KV_E_STATE, "kv_step: cache (stream %d, layer %d) cannot take %d more frames (max_frames %d)", it.stream, it.layer, n_frames, c.max_frames);
   }
   hipStream_t st = (hipStream_t)hip_stream;
   h->timing_now = with_timing && h->timing_mask != 0 && (h->step_calls % h->timing_every) == 0;
@@ -439,23 +463,24 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t 
       it.cache = (int32_t)ci;
       it.t_c = cs.t_c;
       it.cur = cs.cur;
-      it.prune = (!g0.uncompressed && cs.t_c + g0.n > g0.budget) ? 1 : 0;
+      it.prune = (!g0.uncompressed && cs.t_c + n_new > g0.budget) ? 1 : 0;
       it.frame = cs.frames;
       it.g0_host = cs.t_c / g0.k_group;
       it.pad0 = it.pad1 = 0;
       any_prune |= it.prune != 0;
       max_tc = std::max(max_tc, cs.t_c);
-      max_tnew = std::max(max_tnew, std::min(cs.t_c + g0.n, g0.budget));
-      const int tiles = (cs.t_c + kTileK - 1) / kTileK + (g0.n + kTileK - 1) / kTileK;
+      const int t_after = std::min(cs.t_c + n_new, g0.budget);
+      max_tnew = std::max(max_tnew, t_after);
+      const int tiles = update_first ? (t_after + kTileK - 1) / kTileK : (cs.t_c + kTileK - 1) / kTileK + (n_new + kTileK - 1) / kTileK;
       min_tiles = std::min(min_tiles, tiles);
     }
     b.g.part_o = part_o;
     b.g.part_ml = part_ml;
-    b.g.n_splits = pick_splits(h, cnt, min_tiles);
+    b.g.n_splits = pick_splits(h, b.g, cnt, min_tiles);
     if (cnt * b.g.n_splits > slots_cap) b.g.n_splits = std::max(1, slots_cap / cnt);
 
     hipStream_t sb = st;          // stream of the cache-update chain
-    if (h->overlap && h->side && !g0.uncompressed) {
+    if (h->overlap && h->side && !g0.uncompressed && !update_first) {
       hipEventRecord(h->ev_fork, st);
       hipStreamWaitEvent(h->side, h->ev_fork, 0);
       sb = h->side;
@@ -487,8 +512,21 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t 
       // and end, so the figure is the kernel's duration as a kernel trace reports it
       hipEvent_t e0 = nullptr, e1 = nullptr;
       timed_pair(h, KV_K_ATTENTION, &e0, &e1);
-      if (g0.meta16) launch_attention16(b, st, e0, e1);
-      else launch_attention(b, 0, st, e0, e1);
+      if (update_first) {
+        // the update above ran on this stream; attention reads the half it wrote, which already holds the frame
+        KvxBatch ba = b;
+        ba.g.own_tiles = 0;
+        for (int i = 0; i < cnt; ++i) {
+          ba.items[i].cur ^= 1;
+          ba.items[i].t_c = std::min(b.items[i].t_c + n_new, g0.budget);
+        }
+        if (g0.meta16) launch_attention16(ba, st, e0, e1);
+        else launch_attention(ba, 0, st, e0, e1);
+      } else if (g0.meta16) {
+        launch_attention16(b, st, e0, e1);
+      } else {
+        launch_attention(b, 0, st, e0, e1);
+      }
     }
     record(h, KV_K_COMBINE, true, st);
     launch_combine(b, st);
@@ -507,12 +545,12 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t 
 
     for (int i = 0; i < cnt; ++i) {
       CacheState& cs = h->caches[(size_t)b.items[i].cache];
-      const int t_all = cs.t_c + g0.n;
+      const int t_all = cs.t_c + n_new;
       cs.last_pruned = b.items[i].prune;
       cs.last_scores_len = b.items[i].prune ? cs.t_c - g0.n : 0;
       if (b.items[i].prune) cs.dropped += t_all - g0.budget;
       cs.t_c = std::min(t_all, g0.budget);
-      cs.frames += 1;
+      cs.frames += n_frames;
       if (!g0.uncompressed) cs.cur ^= 1;
     }
   }
@@ -525,13 +563,26 @@ extern "C" {
 
 int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride, int64_t head_stride, void* hip_stream) {
   if (!h) return KV_E_INVAL;
-  return step_impl(h, n_items, items, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->slots_cap, true);
+  return step_impl(h, n_items, items, 1, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->slots_cap, true);
+}
+
+int kv_step_frames(kv_handle* h, int32_t stream, int32_t layer, int32_t n_frames, const void* q, const void* k, const void* v,
+                   int64_t tok_stride, int64_t head_stride, void* out, void* hip_stream) {
+  if (!h) return KV_E_INVAL;
+  kv_step_item it;
+  it.stream = stream;
+  it.layer = layer;
+  it.q = q;
+  it.k = k;
+  it.v = v;
+  it.out = out;
+  return step_impl(h, 1, &it, n_frames, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->slots_cap, true);
 }
 
 int kv_step_static(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v, int64_t tok_stride,
                    int64_t head_stride, void* out, void* hip_stream) {
   if (!h) return KV_E_INVAL;
-  const Geometry& g = h->geo;
+  const Geometry& g = h->geo;      // its query tiling is that of one frame
   // one (cache, split) slot: [H][n_pad][64] fp32 partial outputs + [H][n_pad][2] fp32 (max, sum), the two parts 256-byte aligned
   const int64_t slot_o = (int64_t)g.H * g.n_pad * kHeadDim * 4, slot_ml = (int64_t)g.H * g.n_pad * 2 * 4;
   const int64_t slots = std::min<int64_t>((int64_t)kStaticScratchBytes / (slot_o + slot_ml + 512), kMaxSplits);
@@ -548,7 +599,7 @@ int kv_step_static(kv_handle* h, int32_t stream, int32_t layer, const void* q, c
   it.k = k;
   it.v = v;
   it.out = out;
-  return step_impl(h, 1, &it, tok_stride, head_stride, hip_stream, part_o, part_ml, (int32_t)slots, false);
+  return step_impl(h, 1, &it, 1, tok_stride, head_stride, hip_stream, part_o, part_ml, (int32_t)slots, false);
 }
 
 int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v, int64_t tok_stride,

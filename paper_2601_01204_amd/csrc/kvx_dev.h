@@ -63,6 +63,9 @@ struct Geometry {
   int64_t out_head_stride;
   int32_t H;
   int32_t n;              // tokens per frame
+  int32_t n_new;          // tokens this call brings: n_frames * n (query rows, own keys, appended tokens)
+  int32_t own_tiles;      // 1: attention reads the call's K/V from the inputs behind the cache; 0: they are in the cache already
+                          //    (update-first order: items then name the updated half and its length)
   int32_t n_special;
   int32_t pool_group;
   int32_t n_pooled;
@@ -74,7 +77,7 @@ struct Geometry {
   int32_t out_f32;        // 1: out is fp32, 0: bf16
   int32_t uncompressed;   // 1: bf16 cache without pruning or quantisation
   int32_t n_splits;
-  int32_t n_pad;          // query rows padded to n_qtiles * q_blocks * 32
+  int32_t n_pad;          // query rows of this call padded to n_qtiles * q_blocks * 32
   int32_t n_qtiles;       // query tiles (attention workgroups per head and key split)
   int32_t q_blocks;       // 32-row query blocks per tile (<= 12, one per wave)
   float scale_log2;       // softmax scale * log2(e)

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
   const int t_c = it.t_c;
-  const int t_new = min(t_c + g.n, g.budget);
+  const int t_new = min(t_c + g.n_new, g.budget);
   const int p0 = blockIdx.x * kTileK;
   if (p0 >= t_new) return;
   const uint8_t* cur = cache_half(g, it.cache, it.cur);
@@ -386,8 +386,8 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_
   const Item it = b.items[blockIdx.z];
   const int h = blockIdx.y;
   const int t_c = it.t_c;
-  const int t_new = min(t_c + g.n, g.budget);
-  const int t_keep = t_new - g.n;          // survivors
+  const int t_new = min(t_c + g.n_new, g.budget);
+  const int t_keep = t_new - g.n_new;      // survivors
   const int tid = threadIdx.x;
   const uint8_t* cur = cache_half(g, it.cache, it.cur);
   uint8_t* nxt = cache_half(g, it.cache, it.cur ^ 1);
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_
   const int lanes_per_group = 4 / ngv;     // 4 or 2 lanes share one value group
   const int r = tid >> 2, cb = tid & 3;
   const int i_new = ((int)blockIdx.x - n_copy_blocks) * kTileK + r;     // token of the new frame
-  const bool active = i_new < g.n;         // uniform over each group of 4 lanes
+  const bool active = i_new < g.n_new;     // uniform over each group of 4 lanes
   const int p = t_keep + i_new;
   const int gv = cb / lanes_per_group;
   float x[16];
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(256) void append_bf16_kernel(const KvxBatch b) {
   const int h = blockIdx.y;
   const int i = blockIdx.x * 32 + (threadIdx.x >> 3);
   const int c8 = (threadIdx.x & 7) * 8;
-  if (i >= g.n) return;
+  if (i >= g.n_new) return;
   uint8_t* base = cache_half(g, it.cache, 0);
   const int64_t off = (int64_t)i * g.tok_stride + (int64_t)h * g.head_stride + c8;
   const int64_t dsto = ((int64_t)h * g.t_cap + it.t_c + i) * kHeadDim + c8;
@@ -525,8 +525,8 @@ void launch_rebuild_k(const KvxBatch& b, int max_tnew, hipStream_t st) {
 
 void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st) {
   const int rows_per_block = 256 / (b.g.v_bits / 2);           // 16 bytes of codes per lane
-  const int n_copy_blocks = (std::max(max_tnew - b.g.n, 0) + rows_per_block - 1) / rows_per_block;
-  dim3 grid(n_copy_blocks + (b.g.n + kTileK - 1) / kTileK, b.g.H, b.n_items);
+  const int n_copy_blocks = (std::max(max_tnew - b.g.n_new, 0) + rows_per_block - 1) / rows_per_block;
+  dim3 grid(n_copy_blocks + (b.g.n_new + kTileK - 1) / kTileK, b.g.H, b.n_items);
   if (b.g.meta16) {
     switch (b.g.v_bits) {
       case 2: hipLaunchKernelGGL((rebuild_v_kernel<2, true>), grid, dim3(256), 0, st, b, n_copy_blocks); break;
@@ -543,7 +543,7 @@ void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st) {
 }
 
 void launch_append_bf16(const KvxBatch& b, hipStream_t st) {
-  dim3 grid((b.g.n + 31) / 32, b.g.H, b.n_items);
+  dim3 grid((b.g.n_new + 31) / 32, b.g.H, b.n_items);
   hipLaunchKernelGGL(append_bf16_kernel, grid, dim3(256), 0, st, b);
 }
 

@@ -20,14 +20,16 @@ __global__ __launch_bounds__(512) void pool_rows_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.y];
   if (!it.prune) return;
+  // pooled row -> (frame of the call, row within the frame): every frame is pooled by itself
   const int row = blockIdx.x;
+  const int fr = row / g.n_pooled, rr = row - fr * g.n_pooled;
   int a, e;
-  if (row < g.n_special) {
-    a = row;
-    e = row + 1;
+  if (rr < g.n_special) {
+    a = fr * g.n + rr;
+    e = a + 1;
   } else {
-    a = g.n_special + (row - g.n_special) * g.pool_group;
-    e = min(a + g.pool_group, g.n);
+    a = fr * g.n + g.n_special + (rr - g.n_special) * g.pool_group;
+    e = min(a + g.pool_group, (fr + 1) * g.n);
   }
   __shared__ __attribute__((aligned(16))) float pooled[64][kHeadDim];     // up to 64 heads
   const int h = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 8;
@@ -90,8 +92,9 @@ __global__ __launch_bounds__(1024) void pool_mean_kernel(const KvxBatch b) {
   __shared__ __attribute__((aligned(16))) float rows[kMeanRows][kHeadDim];
   const int tid = threadIdx.x;
   float acc = 0.f;
-  for (int r0 = 0; r0 < g.n_pooled; r0 += kMeanRows) {
-    const int cnt = min(kMeanRows, g.n_pooled - r0);
+  const int n_rows = g.n_pooled * (g.n_new / g.n);          // the pooled rows of all the call's frames, in frame order
+  for (int r0 = 0; r0 < n_rows; r0 += kMeanRows) {
+    const int cnt = min(kMeanRows, n_rows - r0);
     // 16 float4 per row: threads 0..1023 cover 64 rows per step
 #pragma unroll
     for (int k = 0; k < kMeanRows / 64; ++k) {
@@ -104,7 +107,7 @@ __global__ __launch_bounds__(1024) void pool_mean_kernel(const KvxBatch b) {
     }
     __syncthreads();
   }
-  if (tid < kHeadDim) reinterpret_cast<float*>(sc + g.sl.qt)[tid] = acc / (float)g.n_pooled;
+  if (tid < kHeadDim) reinterpret_cast<float*>(sc + g.sl.qt)[tid] = acc / (float)n_rows;
 }
 
 // One row's codes as floats, channel by channel, through byte conversions (v_cvt_f32_ubyteN): 4-bit codes are
@@ -221,7 +224,7 @@ __global__ __launch_bounds__(256) void score_dots_kernel(const KvxBatch b) {
 }
 
 void launch_pool(const KvxBatch& b, hipStream_t st) {
-  hipLaunchKernelGGL(pool_rows_kernel, dim3(b.g.n_pooled, b.n_items), dim3(std::max(64, 8 * b.g.H)), 0, st, b);
+  hipLaunchKernelGGL(pool_rows_kernel, dim3(b.g.n_pooled * (b.g.n_new / b.g.n), b.n_items), dim3(std::max(64, 8 * b.g.H)), 0, st, b);
   hipLaunchKernelGGL(pool_mean_kernel, dim3(b.n_items), dim3(1024), 0, st, b);
 }
 

@@ -83,10 +83,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   const Item it = b.items[blockIdx.x];
   if (!it.prune) return;
   const int n = g.n, t_c = it.t_c;
+  const int n_cur = g.n_new;             // the call's tokens: always kept
   const int M = t_c - n;                 // middle tokens: cache positions n .. t_c - 1
-  const int T = t_c + n;
+  const int T = t_c + n_cur;
   const int n_drop = T - g.budget;       // >= 1
-  const int k_keep = M - n_drop;         // = budget - 2n
+  const int k_keep = M - n_drop;         // = budget - n - n_cur
   uint8_t* sc = cache_scratch(g, it.cache);
   const uint32_t* keys = reinterpret_cast<const uint32_t*>(sc + g.sl.keys);
   int32_t* keep = reinterpret_cast<int32_t*>(sc + g.sl.keep);
@@ -204,11 +205,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
     }
   }
   if (first_drop < T) atomicMin(&sh_p0, first_drop);
-  // first frame and current frame are always kept
-  for (int i = tid; i < n; i += kSelThreads) {
-    keep[i] = i;
-    keep[n + k_keep + i] = t_c + i;
-  }
+  // the first frame and the call's own tokens are always kept
+  for (int i = tid; i < n; i += kSelThreads) keep[i] = i;
+  for (int i = tid; i < n_cur; i += kSelThreads) keep[n + k_keep + i] = t_c + i;
   __syncthreads();
   if (tid == 0) {
     sel[0] = sh_p0;

@@ -20,7 +20,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     lib = kvx.load_library()
     names = _declared_functions()
-    assert {"kv_init", "kv_step", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_destroy",
+    assert {"kv_init", "kv_step", "kv_step_frames", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_destroy",
             "kv_last_error", "kv_set_timing", "kv_read_timing", "kv_set_option", "kv_import", "kv_probe_mfma_bf16",
             "kv_probe_copy"} <= set(names)
     for name in names:
@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 def _cfg(**kw):
     base = dict(n_streams=1, n_layers=1, n_heads=4, head_dim=64, tokens_per_frame=69, n_special=5, pool_group=16,
                 budget_tokens=256, k_bits=4, k_group=64, v_bits=4, v_group=64, in_dtype=kvx.KV_BF16,
-                out_dtype=kvx.KV_BF16, mode=kvx.KV_COMPRESSED, max_frames=0, softmax_scale=0.0, meta_format=0)
+                out_dtype=kvx.KV_BF16, mode=kvx.KV_COMPRESSED, max_frames=0, softmax_scale=0.0, meta_format=0, max_frames_per_step=1, order=0)
     base.update(kw)
     c = kvx.KvConfig()
     for k, v in base.items():
@@ -57,6 +57,10 @@ def _cfg(**kw):
     (dict(n_streams=0), -1),
     (dict(budget_tokens=40000), -3),
     (dict(meta_format=2), -1),
+    (dict(order=2), -1),
+    (dict(max_frames_per_step=-1), -1),
+    (dict(max_frames_per_step=3, budget_tokens=4 * 69 - 1), -1),   # first frame + a full chunk must fit the budget
+    (dict(max_frames_per_step=2, order=1), -1),
     (dict(meta_format=1, k_bits=8), -1),          # 16-bit metadata: 2- or 4-bit keys
     (dict(meta_format=1, in_dtype=kvx.KV_F32), -1),
 ])
