@@ -188,26 +188,51 @@ def oracle_baseline(torch, run, frames_total, steady, meta16=False):
 
 def aux_vggt_layer(torch, kvx, si, dev, steps):
     """One layer cache of the second configuration (budget 8192) through kv_step: the latency a model whose
-    layers run one after the other sees per layer."""
+    layers run one after the other sees per layer; the same with 16-bit metadata, with four frames per call
+    (kv_step_frames, frame-wise causal mask inside the chunk) and in the update-first order."""
     w = si.WORKLOADS["vggt_layer"]
-    run = StackRun(torch, kvx, w, dev, 1, 1, 12, 101)
-    fill = -(-w.budget_tokens // w.tokens_per_frame) + 1
-    run.run(fill + 3)
-    run.h.set_option("timing_every", 8)
-    run.h.set_timing(1)
-    dt = run.timed(steps)
-    ms, cnt = run.h.read_timing()["attention"]
-    run.h.set_timing(0)
-    us = kernel_times(run, min(steps, 50))
-    st = run.h.stats()
-    a_us = ms * 1e3 / max(cnt, 1)
-    out = {"workload": "vggt_layer: 1 layer, budget 8192, INT4/INT4 g64, kv_step per frame",
-           "frames/s": round(steps / dt, 1), "ms_per_step": round(dt * 1e3 / steps, 4),
-           "attention_us": round(a_us, 2), "attention_TFLOP/s": round(attention_flops(w) / (a_us * 1e-6) / 1e12, 1),
-           "attention_frac": round(attention_flops(w) / (a_us * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS, 4),
-           "kernel_us": {k: round(v, 2) for k, v in us.items()},
-           "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "allocated": st["bytes_allocated"]}}
-    run.close()
+    n, H, d = w.tokens_per_frame, w.n_heads, w.head_dim
+    fill = -(-w.budget_tokens // n) + 1
+    out = {"workload": "vggt_layer: 1 layer, budget 8192, INT4/INT4 g64, one cache per call"}
+    variants = (("kv_step", dict(), 1), ("kv_step_meta16", dict(meta_format=kvx.KV_META_F16), 1),
+                ("kv_step_frames_4", dict(max_frames_per_step=4), 4),
+                ("kv_step_frames_4_meta16", dict(max_frames_per_step=4, meta_format=kvx.KV_META_F16), 4),
+                ("kv_step_update_first", dict(order=kvx.KV_PRUNE_THEN_ATTEND), 1))
+    for name, extra, F in variants:
+        run = StackRun(torch, kvx, w, dev, 1, 1, 12, 101, **extra)
+        q, k, v = run.frames[0]
+        o = torch.empty((F * n, H, d), dtype=torch.bfloat16, device=dev)
+
+        def call(i):
+            r = (i * F) % 12
+            run.h.step_frames(F, q[r:r + F].reshape(F * n, H, d), k[r:r + F].reshape(F * n, H, d), v[r:r + F].reshape(F * n, H, d),
+                              o, hip_stream=run.stream)
+        calls = max(steps // F, 10)
+        for i in range(fill + 3):
+            call(i)
+        run.h.set_option("timing_every", 8 if F == 1 else 1)
+        run.h.set_timing(1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(calls):
+            call(i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ms, cnt = run.h.read_timing()["attention"]
+        run.h.set_timing(0)
+        a_us = ms * 1e3 / max(cnt, 1)
+        # attention flops of a call: every frame's queries over the cache and the chunk's frames up to their own
+        flops = sum(4.0 * n * (w.budget_tokens + (f + 1) * n) * d * H for f in range(F))
+        if name == "kv_step_update_first":
+            flops = 4.0 * n * w.budget_tokens * d * H
+        st = run.h.stats()
+        out[name] = {"frames/s": round(F * calls / dt, 1), "ms_per_call": round(dt * 1e3 / calls, 4), "attention_us": round(a_us, 2),
+                     "attention_TFLOP/s": round(flops / (a_us * 1e-6) / 1e12, 1),
+                     "attention_frac": round(flops / (a_us * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS, 4),
+                     "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "allocated": st["bytes_allocated"]}}
+        if name == "kv_step":
+            out[name]["kernel_us"] = {kk: round(vv, 2) for kk, vv in kernel_times(run, min(steps, 50)).items()}
+        run.close()
     return out
 
 
@@ -372,6 +397,28 @@ def main():
 
     if not args.no_aux:
         aux = {}
+        # the same 24-layer step with the other quantiser metadata format
+        other = "f32" if meta16 else "f16"
+        run2 = StackRun(torch, kvx, w, dev, 1, NL, 20, 102, meta_format=kvx.KV_META_F32 if meta16 else kvx.KV_META_F16)
+        run2.run(warm)
+        run2.h.set_option("timing_every", 1)
+        run2.h.set_timing(1)
+        steps2 = min(args.steps, 30)
+        dt2 = run2.timed(steps2)
+        ms2, cnt2 = run2.h.read_timing()["attention"]
+        run2.h.set_timing(0)
+        us2 = kernel_times(run2, min(args.steps, 10))
+        st2 = run2.h.stats()
+        a2 = ms2 * 1e-3 / max(cnt2, 1)
+        aux["vggt_stack_meta_" + other] = {
+            "workload": "the headline step with " + ("fp32 scale + int32 zero-point" if meta16 else "16-bit scale + zero-point") + " metadata",
+            "frames/s": round(steps2 / dt2, 2), "ms_per_step": round(dt2 * 1e3 / steps2, 4),
+            "attention_us": round(a2 * 1e6, 2), "attention_TFLOP/s": round(flops / a2 / 1e12, 1),
+            "attention_frac": round(flops / a2 / 1e12 / PEAK_MFMA_TFLOPS, 4),
+            "kernel_us": {k: round(v, 2) for k, v in us2.items()},
+            "hbm_kernels": hbm_report(w, NL, us2, 8 if meta16 else 4),
+            "kv_bytes": {"live_per_cache": st2["bytes_live_per_cache"], "allocated": st2["bytes_allocated"]}}
+        run2.close()
         aux["vggt_layer"] = aux_vggt_layer(torch, kvx, si, dev, max(args.steps, 50))
         aux["vggt_long"] = aux_vggt_long(torch, kvx, si, dev, args.long_frames, (100, 250, 500))
         aux["vggt_hires"] = aux_vggt_hires(torch, kvx, si, dev, min(args.steps, 20))

@@ -115,6 +115,7 @@ struct kv_handle {
   int32_t splits_override = 0;
   int32_t n_cus = 256;        // compute units of the device (an attention workgroup occupies one by itself)
   int32_t target_wgs = 192;   // three quarters of the CUs: the rest runs the cache-update chain beside attention
+  bool target_explicit = false;   // set through "attention_target_workgroups": used as given
   int device = 0;
   // second stream for the score / prune / re-quantise chain, which is independent of the
   // attention launches of the same step (both only read the current cache half)
@@ -202,7 +203,7 @@ int validate(const kv_config* c) {
 // is rounds x (tiles per workgroup + a fixed per-workgroup cost of about three tiles for the
 // first loads and the partial-result store), and the split count with the smallest
 // estimate wins (fewer splits on ties: less merge traffic).
-int pick_splits(const kv_handle* h, const Geometry& g, int n_items, int min_tiles) {
+int pick_splits(const kv_handle* h, const Geometry& g, int n_items, int min_tiles, int target_wgs) {
   int s;
   if (h->splits_override > 0) {
     s = h->splits_override;
@@ -210,11 +211,11 @@ int pick_splits(const kv_handle* h, const Geometry& g, int n_items, int min_tile
     const int64_t base = (int64_t)n_items * g.H * g.n_qtiles;
     const int tiles = std::max(1, std::min(min_tiles, 1 << 20));
     // up to two rounds' worth of workgroups, and at least four splits to choose from
-    const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, (2 * (int64_t)h->target_wgs) / base));
+    const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, (2 * (int64_t)target_wgs) / base));
     double best = 0.0;
     s = 1;
     for (int c = 1; c <= cap; ++c) {
-      const int64_t rounds = (base * c + h->target_wgs - 1) / h->target_wgs;
+      const int64_t rounds = (base * c + target_wgs - 1) / target_wgs;
       const double cost = (double)rounds * ((double)tiles / c + 3.0) + (c > 1 ? 1.0 : 0.0);
       if (c == 1 || cost < best * 0.98) { best = cost; s = c; }
     }
@@ -476,11 +477,16 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
     }
     b.g.part_o = part_o;
     b.g.part_ml = part_ml;
-    b.g.n_splits = pick_splits(h, b.g, cnt, min_tiles);
+    // The cache-update chain runs beside attention on the library's second stream when attention alone cannot fill
+    // the chip (fewer workgroup columns than compute units: one or a few caches per call); a launch that fills the
+    // chip several times over gains nothing from sharing it, so there the chain follows attention on the caller's stream.
+    const bool beside = h->overlap && h->side && !g0.uncompressed && !update_first &&
+                        (int64_t)cnt * g0.H * g0.n_qtiles <= (int64_t)h->n_cus;
+    b.g.n_splits = pick_splits(h, b.g, cnt, min_tiles, (beside || h->target_explicit) ? h->target_wgs : h->n_cus);
     if (cnt * b.g.n_splits > slots_cap) b.g.n_splits = std::max(1, slots_cap / cnt);
 
     hipStream_t sb = st;          // stream of the cache-update chain
-    if (h->overlap && h->side && !g0.uncompressed && !update_first) {
+    if (beside) {
       hipEventRecord(h->ev_fork, st);
       hipStreamWaitEvent(h->side, h->ev_fork, 0);
       sb = h->side;
@@ -929,6 +935,7 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
   if (!strcmp(name, "attention_target_workgroups")) {
     if (value < 1 || value > 65536) return fail(h, KV_E_RANGE, "kv_set_option: attention_target_workgroups out of range");
     h->target_wgs = (int32_t)value;
+    h->target_explicit = true;
     return KV_OK;
   }
   return fail(h, KV_E_INVAL, "kv_set_option: unknown option '%s'", name);
