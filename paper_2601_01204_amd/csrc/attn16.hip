@@ -191,6 +191,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
     o[0][r] = 0.f;
     o[1][r] = 0.f;
   }
+  asm volatile("" : "+v"(negm));
 
   // staging role of this thread: rows (key_a, key_a + 1) of the tile, channels [8 co, 8 co + 8)
   const int st = tid & 255;
@@ -325,29 +326,37 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
     };
     auto read_q = [&](int ks) __attribute__((always_inline)) { qf[ks] = __builtin_bit_cast(f16x8, qbase[ks * 64]); };
     const bool own = t >= ntc;                     // the frame's own keys: unscaled, from a zero accumulator
-    f32x16 acc0;
-    if (own) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc0[r] = 0.f;
-    } else {
-      acc0 = negm;
-    }
     read_q(0);
 #pragma unroll
     for (int i = 0; i < kAhead; ++i) read_k(i);
     read_q(1);
     __builtin_amdgcn_s_setprio(1);
+    if (!own) {
+      // cached keys carry the logit factor: the accumulator starts at -m, so S^T leaves the matrix core as s - m
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int ks = i >> 1, mb = i & 1;
-      if (i + kAhead < 8) read_k(i + kAhead);
-      if (mb == 0 && ks + 2 < 4) read_q(ks + 2);
-      s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak[i], qf[ks], ks == 0 ? acc0 : s[mb], 0, 0, 0);
-    }
-    sched_group<0x100, kAhead + 2>();
-    pin_qk_steps<kAhead>(std::make_integer_sequence<int, 8>{});
-    __builtin_amdgcn_s_setprio(0);
-    if (own) {
+      for (int i = 0; i < 8; ++i) {
+        const int ks = i >> 1, mb = i & 1;
+        if (i + kAhead < 8) read_k(i + kAhead);
+        if (mb == 0 && ks + 2 < 4) read_q(ks + 2);
+        if (ks == 0) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak[i], qf[ks], negm, 0, 0, 0);
+        else s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak[i], qf[ks], s[mb], 0, 0, 0);
+      }
+      pin_qk_steps<kAhead>(std::make_integer_sequence<int, 8>{});
+      __builtin_amdgcn_s_setprio(0);
+    } else {
+      f32x16 zero;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int ks = i >> 1, mb = i & 1;
+        if (i + kAhead < 8) read_k(i + kAhead);
+        if (mb == 0 && ks + 2 < 4) read_q(ks + 2);
+        if (ks == 0) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak[i], qf[ks], zero, 0, 0, 0);
+        else s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak[i], qf[ks], s[mb], 0, 0, 0);
+      }
+      pin_qk_steps<kAhead>(std::make_integer_sequence<int, 8>{});
+      __builtin_amdgcn_s_setprio(0);
       const float nm = -m_ref;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
@@ -419,6 +428,7 @@ __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBat
         for (int r = 0; r < 16; ++r) s[mb][r] -= delta;
 #pragma unroll
       for (int r = 0; r < 16; ++r) negm[r] = -m_ref;
+      asm volatile("" : "+v"(negm));     // opaque: the block stays in its registers, it is the accumulator input of every cached tile
       probabilities();
     }
     l_run = l_new;
