@@ -32,7 +32,8 @@ order: update first, attend over codes only); a call may carry a chunk of
 several frames, attended with the frame-wise causal mask and appended as one
 block of current tokens; a short last patch group is averaged over its
 own size; ties in top-k keep the lower cache position and survivors stay in
-ascending position order; rounding is to nearest-even; the zero-point is not
+ascending position order (the slot_stable switch keeps every survivor in its
+slot instead and fills the freed slots with the new tokens); rounding is to nearest-even; the zero-point is not
 clamped (with 16-bit metadata, the meta16 switch, scales are rounded up to their
 storage format before anything is computed from them and zero-points are kept
 to 12 bits); a quantisation group is re-quantised only when its ordered member
@@ -71,6 +72,9 @@ class OracleConfig:
     quant: bool = True               # False: keep fp32 K/V (pruning only)
     requant_v: bool = False          # True: re-quantise V every step (literal reading; diagnostic)
     meta16: bool = False             # True: 16-bit scales and zero-points (see quant_params_meta16_k / _v)
+    slot_stable: bool = False        # True: tokens never move: a pruned token frees its slot and the new tokens fill the
+                                     #       freed slots in ascending order (no compaction); a key group is the 64 (k_group)
+                                     #       consecutive slots and is re-quantised only when it receives a new member
     attend_after_prune: bool = False # True: the other reading of Fig. 2's order: append, prune, quantise, then attend
                                      #       over the compressed cache (current frame in codes, exactly <= L_max keys)
 
@@ -484,6 +488,13 @@ class OracleCache:
         else:
             keep = np.arange(T, dtype=np.int32)
 
+        if c.slot_stable:
+            self._update_slots(keep, T_old, m, ids_all, k_all, k_new, v_new, scale)
+            self.frames += F
+            if c.attend_after_prune:
+                out = attention_fp64(q, self.stored_k(), self.stored_v(), scale)
+            return out
+
         ids_new = ids_all[keep]
         k_fin = k_all[:, keep, :]
         T_fin = keep.shape[0]
@@ -539,6 +550,74 @@ class OracleCache:
             # Eq. 1 over the compressed cache: every key, the current frame's included, is a de-quantised code
             out = attention_fp64(q, self.stored_k(), self.stored_v(), scale)
         return out
+
+
+def _update_slots(self, keep, T_old, m, ids_all, k_all, k_new, v_new, scale):
+    """Slot-stable cache update (the drift-reducing storage of Sec. 3.3's "quantization is applied to the
+    final KV cache" read per group): which tokens survive is the keep set of Sec. 3.2 exactly as in the
+    compacting cache; where they live is not.  A surviving token stays in its slot.  The free slots, the
+    dropped tokens' slots in ascending order followed by the never-used tail [T_old, L_max), receive the
+    call's new tokens in order.  Values, one group per token, are written once.  A key group (k_group
+    consecutive slots) that received no new member keeps its codes, scale and zero-point bit for bit;
+    one that did is re-quantised by Eq. 7-8 over its present members (stored values of the survivors,
+    inputs of the new tokens)."""
+    c = self.cfg
+    L, G = c.budget_tokens, c.k_group
+    kept_old = keep[keep < T_old]
+    if keep.shape[0] < T_old + m:                      # pruned: some cached slots are freed
+        occupied = np.zeros(T_old, dtype=bool)
+        occupied[kept_old] = True
+        free = np.concatenate([np.flatnonzero(~occupied), np.arange(T_old, max(L, T_old))])
+    else:
+        free = np.arange(T_old, T_old + m)
+    assign = free[:m].astype(np.int64)                  # slot of the call's i-th new token
+    assert assign.shape[0] == m, "the budget must hold the first frame and the call's tokens"
+    T_new = max(T_old, int(assign.max()) + 1)
+    new_ids = ids_all[T_old:]
+
+    def grown(a, fill=0):
+        out = np.full(a.shape[:1] + (T_new,) + a.shape[2:], fill, dtype=a.dtype) if a.ndim > 1 else np.full((T_new,), fill, dtype=a.dtype)
+        if a.ndim > 1:
+            out[:, :a.shape[1]] = a
+        else:
+            out[:a.shape[0]] = a
+        return out
+
+    ids = grown(self.ids)
+    ids[assign] = new_ids
+    if not c.quant:
+        K, V = grown(self.K), grown(self.V)
+        K[:, assign] = k_new
+        V[:, assign] = v_new
+        self.K, self.V, self.ids = K, V, ids
+        return
+    vc_new, vs_new, vz_new = quantize_v_tokens(v_new, c.v_bits, c.v_group, c.meta16)
+    Vc, Vs, Vz = grown(self.Vc), grown(self.Vs), grown(self.Vz)
+    Vc[:, assign], Vs[:, assign], Vz[:, assign] = vc_new, vs_new, vz_new
+    k_old = self.stored_k()                             # Eq. 10 of every slot as stored before the call
+    n_groups = (T_new + G - 1) // G
+    H, d = c.n_heads, c.head_dim
+    Kc = grown(self.Kc)
+    Ks = np.zeros((H, n_groups, d), dtype=F32)
+    Kz = np.zeros((H, n_groups, d), dtype=np.int32)
+    Ks[:, :self.Ks.shape[1]] = self.Ks
+    Kz[:, :self.Kz.shape[1]] = self.Kz
+    slot_token = np.full(T_new, -1, dtype=np.int64)     # index of the new token a slot receives, or -1
+    slot_token[assign] = np.arange(m)
+    for gidx in np.unique(assign // G):
+        a, b = gidx * G, min((gidx + 1) * G, T_new)
+        vals = np.empty((H, b - a, d), dtype=F32)
+        for j, slot in enumerate(range(a, b)):
+            vals[:, j] = k_new[:, slot_token[slot]] if slot_token[slot] >= 0 else k_old[:, slot]
+        codes, s_, z_ = quantize_k_group(vals, c.k_bits, logit_scale_log2(scale) if c.meta16 else None)
+        Kc[:, a:b], Ks[:, gidx], Kz[:, gidx] = codes, s_, z_
+        self.k_groups_requantised += 1
+    self.Kc, self.Ks, self.Kz = Kc, Ks, Kz
+    self.Vc, self.Vs, self.Vz = Vc, Vs, Vz
+    self.ids = ids
+
+
+OracleCache._update_slots = _update_slots
 
 
 def reference_full_attention(frames_qkv, upto: int, scale: float) -> np.ndarray:
