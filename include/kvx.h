@@ -66,6 +66,19 @@ enum kv_order {
                             /* codes like every other token).  One frame per call.                              */
 };
 
+enum kv_layout {
+  KV_LAYOUT_COMPACT = 0,    /* survivors are compacted in ascending position order into the other half of a   */
+                            /* double buffer; every key group behind the first dropped token changes members   */
+                            /* and is re-quantised (Sec. 3.3: quantisation applied to the final cache)         */
+  KV_LAYOUT_SLOTS = 1       /* tokens never move: a pruned token frees its slot, the call's new tokens fill    */
+                            /* the freed slots in ascending order (then the never-used tail); one buffer, in   */
+                            /* place; values and ids of survivors are not touched; a key group, k_group        */
+                            /* consecutive slots, is re-quantised by Eq. 7-8 only when it received a new       */
+                            /* member, every other group keeps codes, scale and zero-point bit for bit.  The   */
+                            /* keep set of Sec. 3.2 is the same rule (ties keep the lower slot).  kv_export    */
+                            /* returns ids in slot order.                                                      */
+};
+
 enum kv_mode {
   KV_COMPRESSED = 0,        /* pruned + quantised cache (the paper's method)                */
   KV_UNCOMPRESSED_BF16 = 1  /* baseline: bf16 cache that grows by n tokens per frame,       */
@@ -95,6 +108,7 @@ typedef struct kv_config {
   int32_t max_frames_per_step; /* most frames one kv_step_frames call may carry (0 or 1: one); */
                             /* budget_tokens must be >= (1 + max_frames_per_step) * tokens_per_frame */
   int32_t order;            /* kv_order                                                        */
+  int32_t layout;           /* kv_layout                                                       */
 } kv_config;
 
 typedef struct kv_handle kv_handle;

@@ -10,6 +10,7 @@ KV_BF16, KV_F32 = 0, 1
 KV_COMPRESSED, KV_UNCOMPRESSED_BF16 = 0, 1
 KV_META_F32, KV_META_F16 = 0, 1
 KV_ATTEND_THEN_PRUNE, KV_PRUNE_THEN_ATTEND = 0, 1
+KV_LAYOUT_COMPACT, KV_LAYOUT_SLOTS = 0, 1
 KERNEL_NAMES = ["attention", "combine", "pool", "score", "select", "rebuild_k", "rebuild_v"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -23,7 +24,7 @@ class KvConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_streams", "n_layers", "n_heads", "head_dim", "tokens_per_frame", "n_special", "pool_group",
         "budget_tokens", "k_bits", "k_group", "v_bits", "v_group", "in_dtype", "out_dtype", "mode", "max_frames")] + [
-        ("softmax_scale", C.c_float), ("meta_format", C.c_int32), ("max_frames_per_step", C.c_int32), ("order", C.c_int32)]
+        ("softmax_scale", C.c_float), ("meta_format", C.c_int32), ("max_frames_per_step", C.c_int32), ("order", C.c_int32), ("layout", C.c_int32)]
 
 
 class KvStepItem(C.Structure):
@@ -119,7 +120,7 @@ class KvHandle:
         c = KvConfig()
         defaults = dict(n_streams=1, n_layers=1, head_dim=64, pool_group=16, k_bits=4, k_group=64, v_bits=4, v_group=64,
                         in_dtype=KV_BF16, out_dtype=None, mode=KV_COMPRESSED, max_frames=0, softmax_scale=0.0, budget_tokens=0,
-                        meta_format=KV_META_F32, max_frames_per_step=1, order=KV_ATTEND_THEN_PRUNE)
+                        meta_format=KV_META_F32, max_frames_per_step=1, order=KV_ATTEND_THEN_PRUNE, layout=KV_LAYOUT_COMPACT)
         defaults.update(cfg)
         if defaults["out_dtype"] is None:
             defaults["out_dtype"] = defaults["in_dtype"]

@@ -178,6 +178,8 @@ int validate(const kv_config* c) {
     if (c->k_bits != 2 && c->k_bits != 4) return fail(nullptr, KV_E_INVAL, "kv_init: KV_META_F16 needs k_bits of 2 or 4 (the key products are exact in half precision up to 4-bit codes)");
     if (c->in_dtype != KV_BF16) return fail(nullptr, KV_E_INVAL, "kv_init: KV_META_F16 needs in_dtype KV_BF16");
   }
+  if (c->layout != KV_LAYOUT_COMPACT && c->layout != KV_LAYOUT_SLOTS) return fail(nullptr, KV_E_INVAL, "kv_init: layout must be KV_LAYOUT_COMPACT or KV_LAYOUT_SLOTS");
+  if (c->layout == KV_LAYOUT_SLOTS && c->mode != KV_COMPRESSED) return fail(nullptr, KV_E_INVAL, "kv_init: KV_LAYOUT_SLOTS applies to the compressed cache");
   if (c->order != KV_ATTEND_THEN_PRUNE && c->order != KV_PRUNE_THEN_ATTEND) return fail(nullptr, KV_E_INVAL, "kv_init: order must be KV_ATTEND_THEN_PRUNE or KV_PRUNE_THEN_ATTEND");
   if (c->max_frames_per_step < 0 || c->max_frames_per_step > 64) return fail(nullptr, KV_E_INVAL, "kv_init: max_frames_per_step must be in [0, 64]");
   if (c->order == KV_PRUNE_THEN_ATTEND && (c->mode != KV_COMPRESSED || c->max_frames_per_step > 1))
@@ -296,6 +298,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   g.out_f32 = c.out_dtype == KV_F32;
   g.uncompressed = unc;
   g.meta16 = c.meta_format == KV_META_F16;
+  g.slots = c.layout == KV_LAYOUT_SLOTS;
   h->f_max = std::max(1, c.max_frames_per_step);
   g.own_tiles = 1;
   // buffers are sized for the largest call; n_pad only grows with the row count
@@ -323,7 +326,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   L.v_meta = off;  off = align_up(off + (unc ? 0 : (int64_t)g.H * g.t_cap * (kHeadDim / g.v_group) * v_meta_elt), 256);
   L.ids = off;     off = align_up(off + (int64_t)g.t_cap * 4, 256);
   L.half_bytes = off;
-  L.cache_bytes = unc ? off : 2 * off;
+  L.cache_bytes = (unc || g.slots) ? off : 2 * off;
 
   ScratchLayout& S = g.sl;
   off = 0;
@@ -333,6 +336,8 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   S.scores = off; off = align_up(off + (unc ? 0 : (int64_t)g.t_cap * 4), 256);
   S.keys = off;   off = align_up(off + (unc ? 0 : (int64_t)g.t_cap * 4), 256);
   S.keep = off;   off = align_up(off + (unc ? 0 : (int64_t)g.t_cap * 4), 256);
+  S.newtok = off; off = align_up(off + (g.slots ? (int64_t)g.t_cap * 4 : 0), 256);
+  S.assign = off; off = align_up(off + (g.slots ? (int64_t)h->f_max * g.n * 4 : 0), 256);
   S.sel = off;    off = align_up(off + 64, 256);
   S.bytes = off;
 
@@ -505,12 +510,14 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
         launch_select(b, max_tc, sb);
         record(h, KV_K_SELECT, false, sb);
       }
-      record(h, KV_K_REBUILD_K, true, sb);
-      launch_rebuild_k(b, max_tnew, sb);
-      record(h, KV_K_REBUILD_K, false, sb);
-      record(h, KV_K_REBUILD_V, true, sb);
-      launch_rebuild_v(b, max_tnew, sb);
-      record(h, KV_K_REBUILD_V, false, sb);
+      if (!g0.slots || update_first) {
+        record(h, KV_K_REBUILD_K, true, sb);
+        launch_rebuild_k(b, max_tnew, sb);
+        record(h, KV_K_REBUILD_K, false, sb);
+        record(h, KV_K_REBUILD_V, true, sb);
+        launch_rebuild_v(b, max_tnew, sb);
+        record(h, KV_K_REBUILD_V, false, sb);
+      }
     }
     if (h->debug_checks) launch_check_finite(b, st);
     {
@@ -523,7 +530,7 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
         KvxBatch ba = b;
         ba.g.own_tiles = 0;
         for (int i = 0; i < cnt; ++i) {
-          ba.items[i].cur ^= 1;
+          if (!g0.slots) ba.items[i].cur ^= 1;
           ba.items[i].t_c = std::min(b.items[i].t_c + n_new, g0.budget);
         }
         if (g0.meta16) launch_attention16(ba, st, e0, e1);
@@ -546,6 +553,15 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
       hipEventRecord(h->ev_join, sb);
       hipStreamWaitEvent(st, h->ev_join, 0);
     }
+    if (g0.slots && !update_first) {
+      // the slot layout is updated in place: the writers follow attention, which reads the same buffer
+      record(h, KV_K_REBUILD_K, true, st);
+      launch_rebuild_k(b, max_tnew, st);
+      record(h, KV_K_REBUILD_K, false, st);
+      record(h, KV_K_REBUILD_V, true, st);
+      launch_rebuild_v(b, max_tnew, st);
+      record(h, KV_K_REBUILD_V, false, st);
+    }
     hipError_t le = hipGetLastError();
     if (le != hipSuccess) return fail(h, KV_E_HIP, "kv_step: launch failed: %s", hipGetErrorString(le));
 
@@ -557,7 +573,7 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
       if (b.items[i].prune) cs.dropped += t_all - g0.budget;
       cs.t_c = std::min(t_all, g0.budget);
       cs.frames += n_frames;
-      if (!g0.uncompressed) cs.cur ^= 1;
+      if (!g0.uncompressed && !g0.slots) cs.cur ^= 1;
     }
   }
   return KV_OK;
@@ -626,7 +642,7 @@ int kv_stats(kv_handle* h, kv_stats_t* s) {
   if (hipDeviceSynchronize() != hipSuccess) return fail(h, KV_E_HIP, "kv_stats: %s", hipGetErrorString(hipGetLastError()));
   const Geometry& g = h->geo;
   const int64_t nc = (int64_t)h->caches.size();
-  const int64_t halves = g.uncompressed ? 1 : 2;
+  const int64_t halves = (g.uncompressed || g.slots) ? 1 : 2;
   memset(s, 0, sizeof *s);
   s->bytes_allocated = h->bytes_arena + h->bytes_scratch + h->bytes_part;
   s->bytes_k_codes = nc * halves * ((int64_t)g.H * g.t_cap * kHeadDim * g.k_bits / 8);

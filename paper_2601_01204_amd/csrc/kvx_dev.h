@@ -46,6 +46,8 @@ struct ScratchLayout {
   int64_t scores;     // [t_cap] float: importance score of middle tokens (index = cache position - n)
   int64_t keys;       // [t_cap] uint32: order-preserving image of the scores
   int64_t keep;       // [t_cap] int32: kept positions, ascending
+  int64_t newtok;     // [t_cap] int32, slot layout: index of the call's token a slot receives, -1 for a slot whose token stays
+  int64_t assign;     // [tokens of the largest call] int32, slot layout: slot of the call's i-th token
   int64_t sel;        // [16] int32: [0] first dropped position, [1] first rebuilt key group, [2] groups rebuilt (running), [3] kept middle tokens, [5] groups quantised with a zero-point beyond +-2^20 (running), [6] non-finite input seen (debug checks)
   int64_t bytes;
 };
@@ -83,6 +85,7 @@ struct Geometry {
   float scale_log2;       // softmax scale * log2(e)
   float inv_scale_log2;   // fp32(1 / scale_log2): s = a * inv_scale_log2 in the 16-bit metadata format
   int32_t meta16;         // 1: 16-bit scales and zero-points
+  int32_t slots;          // 1: slot-stable layout (one buffer, tokens never move), 0: compacting double buffer
 };
 
 struct Item {

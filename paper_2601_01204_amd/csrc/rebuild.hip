@@ -178,7 +178,12 @@ __device__ __forceinline__ void load_input16(const void* base, int64_t off, int 
 // same ordered members as before and is copied verbatim; every other group is rebuilt
 // from the fp32 values of its members: de-quantised codes for surviving tokens, input
 // values for the new frame.
-template <int B, bool M16>
+// Slot layout (SLOTS): the block's 64 positions are 64 consecutive slots of the one buffer; a row keeps its token
+// unless the keep/drop decision freed it (newtok >= 0) or it lies in the never-used tail, and then takes the call's
+// token newtok; a group that received no token is left as it is (the whole block returns early when neither of
+// its groups did), every other group is rebuilt in place: each thread reads its own row piece before any write,
+// and the group's old scale and zero-point are read before the second barrier and replaced after it.
+template <int B, bool M16, bool SLOTS>
 __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
   const Item it = b.items[blockIdx.z];
@@ -188,11 +193,10 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   const int p0 = blockIdx.x * kTileK;
   if (p0 >= t_new) return;
   const uint8_t* cur = cache_half(g, it.cache, it.cur);
-  uint8_t* nxt = cache_half(g, it.cache, it.cur ^ 1);
+  uint8_t* nxt = cache_half(g, it.cache, SLOTS ? it.cur : it.cur ^ 1);
   uint8_t* sc = cache_scratch(g, it.cache);
   const int32_t* keep = reinterpret_cast<const int32_t*>(sc + g.sl.keep);
   int32_t* sel = reinterpret_cast<int32_t*>(sc + g.sl.sel);
-  const int g0 = it.prune ? sel[1] : it.g0_host;      // first group whose membership changed
   constexpr int kRow = 8 * B;                          // bytes per key row
   const int levels = (1 << B) - 1;
 
@@ -202,7 +206,23 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   const bool active = p < t_new;
   const int k_shift = g.k_group == 64 ? 6 : 5;       // groups of 64 or 32 tokens
   const int grp = p >> k_shift;
-  const bool carried = grp < g0;
+  __shared__ int touched[2];                           // slot layout: the block's groups that received a token
+  int tok = -1;                                        // slot layout: the call's token this row receives
+  int g0;                                              // compacting layout: first group whose membership changed
+  bool carried;
+  if constexpr (SLOTS) {
+    g0 = 0;
+    if (tid < 2) touched[tid] = 0;
+    __syncthreads();
+    if (active) tok = it.prune ? reinterpret_cast<const int32_t*>(sc + g.sl.newtok)[p] : (p >= t_c ? p - t_c : -1);
+    if (tok >= 0 && cb == 0) touched[r >> k_shift] = 1;      // benign race: every writer stores 1
+    __syncthreads();
+    if (!touched[0] && !touched[1]) return;
+    carried = !touched[r >> k_shift];
+  } else {
+    g0 = it.prune ? sel[1] : it.g0_host;
+    carried = grp < g0;
+  }
 
   __shared__ __attribute__((aligned(16))) float vals[kTileK][kHeadDim + 4];
   __shared__ float pmin[4][kHeadDim], pmax[4][kHeadDim];
@@ -216,7 +236,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) x[e] = 0.f;
   if (active) {
-    const int src = it.prune ? keep[p] : p;
+    const int src = SLOTS ? (tok >= 0 ? t_c + tok : p) : (it.prune ? keep[p] : p);
     if (src < t_c) {
       unpack16<B>(cur + g.lay.k_codes + ((int64_t)h * g.t_cap + src) * kRow + cb * 2 * B, wsrc);
       if (!carried && M16) {
@@ -294,7 +314,11 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
       const int64_t moff = ((int64_t)h * g.g_cap + ggrp) * kHeadDim + (M16 ? meta16_pos(c) : c);
       float s, a16 = 0.f;
       int32_t z;
-      if (ggrp < g0) {
+      const bool group_carried = SLOTS ? !touched[gi] : ggrp < g0;
+      if (SLOTS && group_carried) {
+        s = 1.0f;                       // left as it is, in place: nothing to write, no row of it is quantised
+        z = 0;
+      } else if (group_carried) {
         if constexpr (M16) {
           a16 = half_bits_to_f32(reinterpret_cast<const uint16_t*>(cur + g.lay.k_scale)[moff]);
           s = a16 * g.inv_scale_log2;
@@ -330,7 +354,8 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
       gr[gi][c] = dv.r;
       gz[gi][c] = z;
       if (!dv.safe) unsafe_scales = 1;
-      if constexpr (M16) {
+      if (SLOTS && group_carried) {
+      } else if constexpr (M16) {
         reinterpret_cast<uint16_t*>(nxt + g.lay.k_scale)[moff] = f32_to_half_bits(a16);
         reinterpret_cast<uint16_t*>(nxt + g.lay.k_zero)[moff] = f32_to_half_bits((float)(1024 + z));
       } else {
@@ -343,7 +368,8 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
 
   if (active) {
     uint8_t* dst = nxt + g.lay.k_codes + ((int64_t)h * g.t_cap + p) * kRow + cb * 2 * B;
-    if (carried) {
+    if (SLOTS && carried) {
+    } else if (carried) {
       if constexpr (B == 2) *reinterpret_cast<uint32_t*>(dst) = wsrc[0];
       else if constexpr (B == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(wsrc[0], wsrc[1]);
       else *reinterpret_cast<uint4*>(dst) = make_uint4(wsrc[0], wsrc[1], wsrc[2], wsrc[3]);
@@ -390,7 +416,7 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_
   const int t_keep = t_new - g.n_new;      // survivors
   const int tid = threadIdx.x;
   const uint8_t* cur = cache_half(g, it.cache, it.cur);
-  uint8_t* nxt = cache_half(g, it.cache, it.cur ^ 1);
+  uint8_t* nxt = cache_half(g, it.cache, g.slots ? it.cur : it.cur ^ 1);
   const int32_t* keep = reinterpret_cast<const int32_t*>(cache_scratch(g, it.cache) + g.sl.keep);
   constexpr int kRow = 8 * B;
   const int ngv = kHeadDim / g.v_group;    // 1 or 2
@@ -424,7 +450,9 @@ __global__ __launch_bounds__(256) void rebuild_v_kernel(const KvxBatch b, int n_
   const int r = tid >> 2, cb = tid & 3;
   const int i_new = ((int)blockIdx.x - n_copy_blocks) * kTileK + r;     // token of the new frame
   const bool active = i_new < g.n_new;     // uniform over each group of 4 lanes
-  const int p = t_keep + i_new;
+  // destination: behind the survivors, or (slot layout) the slot the selection assigned, the next unused one while filling
+  int p = t_keep + i_new;
+  if (g.slots && active) p = it.prune ? reinterpret_cast<const int32_t*>(cache_scratch(g, it.cache) + g.sl.assign)[i_new] : t_c + i_new;
   const int gv = cb / lanes_per_group;
   float x[16];
   float mn = INFINITY, mx = -INFINITY;
@@ -511,21 +539,35 @@ __global__ __launch_bounds__(256) void append_bf16_kernel(const KvxBatch b) {
 
 void launch_rebuild_k(const KvxBatch& b, int max_tnew, hipStream_t st) {
   dim3 grid((max_tnew + kTileK - 1) / kTileK, b.g.H, b.n_items);
+#define KVX_RK(B, M, S) hipLaunchKernelGGL((rebuild_k_kernel<B, M, S>), grid, dim3(256), 0, st, b)
+  if (b.g.slots) {
+    if (b.g.meta16) {
+      if (b.g.k_bits == 2) KVX_RK(2, true, true); else KVX_RK(4, true, true);
+    } else {
+      switch (b.g.k_bits) {
+        case 2: KVX_RK(2, false, true); break;
+        case 4: KVX_RK(4, false, true); break;
+        default: KVX_RK(8, false, true); break;
+      }
+    }
+    return;
+  }
   if (b.g.meta16) {
-    if (b.g.k_bits == 2) hipLaunchKernelGGL((rebuild_k_kernel<2, true>), grid, dim3(256), 0, st, b);
-    else hipLaunchKernelGGL((rebuild_k_kernel<4, true>), grid, dim3(256), 0, st, b);
+    if (b.g.k_bits == 2) KVX_RK(2, true, false); else KVX_RK(4, true, false);
     return;
   }
   switch (b.g.k_bits) {
-    case 2: hipLaunchKernelGGL((rebuild_k_kernel<2, false>), grid, dim3(256), 0, st, b); break;
-    case 4: hipLaunchKernelGGL((rebuild_k_kernel<4, false>), grid, dim3(256), 0, st, b); break;
-    default: hipLaunchKernelGGL((rebuild_k_kernel<8, false>), grid, dim3(256), 0, st, b); break;
+    case 2: KVX_RK(2, false, false); break;
+    case 4: KVX_RK(4, false, false); break;
+    default: KVX_RK(8, false, false); break;
   }
+#undef KVX_RK
 }
 
 void launch_rebuild_v(const KvxBatch& b, int max_tnew, hipStream_t st) {
   const int rows_per_block = 256 / (b.g.v_bits / 2);           // 16 bytes of codes per lane
-  const int n_copy_blocks = (std::max(max_tnew - b.g.n_new, 0) + rows_per_block - 1) / rows_per_block;
+  // the slot layout never moves a survivor: only the call's tokens are written
+  const int n_copy_blocks = b.g.slots ? 0 : (std::max(max_tnew - b.g.n_new, 0) + rows_per_block - 1) / rows_per_block;
   dim3 grid(n_copy_blocks + (b.g.n_new + kTileK - 1) / kTileK, b.g.H, b.n_items);
   if (b.g.meta16) {
     switch (b.g.v_bits) {

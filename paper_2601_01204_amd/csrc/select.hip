@@ -196,12 +196,29 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const KvxBatch b) {
   for (int i = c0; i < c1; ++i) kept_cnt += flags[i];
   int out = block_scan_excl(kept_cnt, wave_sums, tot);
   int first_drop = T;
+  // slot layout: the freed slots in ascending order, then the never-used tail, take the call's tokens in order
+  int32_t* newtok = reinterpret_cast<int32_t*>(sc + g.sl.newtok);
+  int32_t* assign = reinterpret_cast<int32_t*>(sc + g.sl.assign);
   for (int i = c0; i < c1; ++i) {
     if (flags[i]) {
       keep[n + out] = n + i;
+      if (g.slots) newtok[n + i] = -1;
       ++out;
-    } else if (first_drop == T) {
-      first_drop = n + i;
+    } else {
+      if (first_drop == T) first_drop = n + i;
+      if (g.slots) {
+        const int d = i - out;             // dropped tokens before this one
+        assign[d] = n + i;
+        newtok[n + i] = d;
+      }
+    }
+  }
+  if (g.slots) {
+    for (int i = tid; i < n; i += kSelThreads) newtok[i] = -1;
+    for (int sl = t_c + tid; sl < g.budget; sl += kSelThreads) {
+      const int d = n_drop + (sl - t_c);
+      assign[d] = sl;
+      newtok[sl] = d;
     }
   }
   if (first_drop < T) atomicMin(&sh_p0, first_drop);

@@ -12,9 +12,9 @@ OUT_MAX_ABS = 2e-2
 OUT_MEAN_ABS = 2e-3
 
 
-def oracle_cfg(w: si.Workload, meta16: bool = False) -> xo.OracleConfig:
+def oracle_cfg(w: si.Workload, meta16: bool = False, slots: bool = False) -> xo.OracleConfig:
     return xo.OracleConfig(w.n_heads, w.head_dim, w.tokens_per_frame, w.n_special, w.pool_group, w.budget_tokens,
-                           w.k_bits, w.k_group, w.v_bits, w.v_group, meta16=meta16)
+                           w.k_bits, w.k_group, w.v_bits, w.v_group, meta16=meta16, slot_stable=slots)
 
 
 def make_handle(w: si.Workload, n_streams=1, n_layers=1, **extra):
@@ -64,12 +64,12 @@ def check_state(ex: dict, cache: xo.OracleCache, what: str):
 
 
 def run_stream(w: si.Workload, frames: int, check_every: int = 1, stream: int = 0, layer: int = 0, handle=None,
-               log=print, meta16: bool = False):
+               log=print, meta16: bool = False, slots: bool = False):
     """Free-running parity: both sides evolve their own cache from the same inputs.  meta16: the
-    16-bit quantiser metadata format on both sides."""
+    16-bit quantiser metadata format on both sides; slots: the slot-stable layout on both sides."""
     import torch
-    h = handle or make_handle(w, meta_format=1 if meta16 else 0)
-    cache = xo.OracleCache(oracle_cfg(w, meta16))
+    h = handle or make_handle(w, meta_format=1 if meta16 else 0, layout=1 if slots else 0)
+    cache = xo.OracleCache(oracle_cfg(w, meta16, slots))
     sigma = si.key_channel_scales(w, stream, layer)
     worst = (0.0, 0.0)
     for t in range(frames):

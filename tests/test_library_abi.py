@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 def _cfg(**kw):
     base = dict(n_streams=1, n_layers=1, n_heads=4, head_dim=64, tokens_per_frame=69, n_special=5, pool_group=16,
                 budget_tokens=256, k_bits=4, k_group=64, v_bits=4, v_group=64, in_dtype=kvx.KV_BF16,
-                out_dtype=kvx.KV_BF16, mode=kvx.KV_COMPRESSED, max_frames=0, softmax_scale=0.0, meta_format=0, max_frames_per_step=1, order=0)
+                out_dtype=kvx.KV_BF16, mode=kvx.KV_COMPRESSED, max_frames=0, softmax_scale=0.0, meta_format=0, max_frames_per_step=1, order=0, layout=0)
     base.update(kw)
     c = kvx.KvConfig()
     for k, v in base.items():
@@ -58,6 +58,8 @@ def _cfg(**kw):
     (dict(budget_tokens=40000), -3),
     (dict(meta_format=2), -1),
     (dict(order=2), -1),
+    (dict(layout=2), -1),
+    (dict(layout=1, mode=kvx.KV_UNCOMPRESSED_BF16, max_frames=4), -1),
     (dict(max_frames_per_step=-1), -1),
     (dict(max_frames_per_step=3, budget_tokens=4 * 69 - 1), -1),   # first frame + a full chunk must fit the budget
     (dict(max_frames_per_step=2, order=1), -1),
