@@ -186,6 +186,33 @@ def oracle_baseline(torch, run, frames_total, steady, meta16=False):
                       f"{w.budget_tokens} tokens), times {run.n_layers} layers"}
 
 
+def stack_variant(torch, kvx, w, dev, NL, warm, steps, meta16, slots, flops):
+    """The headline 24-layer step with another metadata format and / or cache layout."""
+    run2 = StackRun(torch, kvx, w, dev, 1, NL, 20, 102, meta_format=kvx.KV_META_F16 if meta16 else kvx.KV_META_F32,
+                    layout=kvx.KV_LAYOUT_SLOTS if slots else kvx.KV_LAYOUT_COMPACT)
+    run2.run(warm)
+    run2.h.set_option("timing_every", 1)
+    run2.h.set_timing(1)
+    dt2 = run2.timed(steps)
+    ms2, cnt2 = run2.h.read_timing()["attention"]
+    run2.h.set_timing(0)
+    us2 = kernel_times(run2, min(steps, 10))
+    st2 = run2.h.stats()
+    a2 = ms2 * 1e-3 / max(cnt2, 1)
+    out = {"workload": "the headline step with " + ("16-bit scale + zero-point" if meta16 else "fp32 scale + int32 zero-point") +
+                       " metadata, " + ("slot-stable" if slots else "compacting") + " layout",
+           "frames/s": round(steps / dt2, 2), "ms_per_step": round(dt2 * 1e3 / steps, 4),
+           "attention_us": round(a2 * 1e6, 2), "attention_TFLOP/s": round(flops / a2 / 1e12, 1),
+           "attention_frac": round(flops / a2 / 1e12 / PEAK_MFMA_TFLOPS, 4),
+           "kernel_us": {k: round(v, 2) for k, v in us2.items()},
+           "kv_bytes": {"live_per_cache": st2["bytes_live_per_cache"], "allocated": st2["bytes_allocated"],
+                        "allocated_per_cache": st2["bytes_allocated"] // NL}}
+    if not slots:
+        out["hbm_kernels"] = hbm_report(w, NL, us2, 4 if meta16 else 8)
+    run2.close()
+    return out
+
+
 def aux_vggt_layer(torch, kvx, si, dev, steps):
     """One layer cache of the second configuration (budget 8192) through kv_step: the latency a model whose
     layers run one after the other sees per layer; the same with 16-bit metadata, with four frames per call
@@ -316,6 +343,8 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="run the cache update after attention instead of beside it")
     ap.add_argument("--no-aux", action="store_true", help="skip the other configurations (one layer, long stream, high-resolution multi-stream)")
     ap.add_argument("--long-frames", type=int, default=1000, help="frames of the long-stream run in aux")
+    ap.add_argument("--layout", choices=("compact", "slots"), default="compact",
+                    help="cache layout of the headline run: compacting double buffer, or slot-stable single buffer")
     ap.add_argument("--meta", choices=("f32", "f16"), default="f32",
                     help="quantiser metadata format of the headline run: fp32 scale + int32 zero-point, or 16-bit scale + zero-point")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -337,7 +366,9 @@ def main():
     w = si.WORKLOADS["vggt_stack"]
     n, H, d, L, NL = w.tokens_per_frame, w.n_heads, w.head_dim, w.budget_tokens, w.n_layers
     meta16 = args.meta == "f16"
-    run = StackRun(torch, kvx, w, dev, 1, NL, 20, 102, meta_format=kvx.KV_META_F16 if meta16 else kvx.KV_META_F32)
+    slots = args.layout == "slots"
+    run = StackRun(torch, kvx, w, dev, 1, NL, 20, 102, meta_format=kvx.KV_META_F16 if meta16 else kvx.KV_META_F32,
+                   layout=kvx.KV_LAYOUT_SLOTS if slots else kvx.KV_LAYOUT_COMPACT)
     if args.splits:
         run.h.set_option("attention_splits", args.splits)
     if args.no_overlap:
@@ -377,7 +408,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "vggt_stack: 24 layer caches per frame in one kv_step_batched, 16 heads x 64, 1041 tokens/frame, budget "
                                "16384 tokens/layer, INT4 K per-channel g64 / INT4 V per-token g64, " +
-                               ("16-bit scale + zero-point" if meta16 else "fp32 scale + int32 zero-point") + ", steady state",
+                               ("16-bit scale + zero-point" if meta16 else "fp32 scale + int32 zero-point") +
+                               (", slot-stable layout" if slots else ", compacting layout") + ", steady state",
                    "keys_per_step": L + n, "layers": NL, "attention_splits": args.splits or "auto"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_MFMA_TFLOPS, 4), "traffic": attention_traffic("vggt_stack", args.meta),
@@ -397,28 +429,13 @@ def main():
 
     if not args.no_aux:
         aux = {}
-        # the same 24-layer step with the other quantiser metadata format
-        other = "f32" if meta16 else "f16"
-        run2 = StackRun(torch, kvx, w, dev, 1, NL, 20, 102, meta_format=kvx.KV_META_F32 if meta16 else kvx.KV_META_F16)
-        run2.run(warm)
-        run2.h.set_option("timing_every", 1)
-        run2.h.set_timing(1)
-        steps2 = min(args.steps, 30)
-        dt2 = run2.timed(steps2)
-        ms2, cnt2 = run2.h.read_timing()["attention"]
-        run2.h.set_timing(0)
-        us2 = kernel_times(run2, min(args.steps, 10))
-        st2 = run2.h.stats()
-        a2 = ms2 * 1e-3 / max(cnt2, 1)
-        aux["vggt_stack_meta_" + other] = {
-            "workload": "the headline step with " + ("fp32 scale + int32 zero-point" if meta16 else "16-bit scale + zero-point") + " metadata",
-            "frames/s": round(steps2 / dt2, 2), "ms_per_step": round(dt2 * 1e3 / steps2, 4),
-            "attention_us": round(a2 * 1e6, 2), "attention_TFLOP/s": round(flops / a2 / 1e12, 1),
-            "attention_frac": round(flops / a2 / 1e12 / PEAK_MFMA_TFLOPS, 4),
-            "kernel_us": {k: round(v, 2) for k, v in us2.items()},
-            "hbm_kernels": hbm_report(w, NL, us2, 8 if meta16 else 4),
-            "kv_bytes": {"live_per_cache": st2["bytes_live_per_cache"], "allocated": st2["bytes_allocated"]}}
-        run2.close()
+        # the same 24-layer step in the other quantiser metadata format and in the other layout
+        variants = [("meta_" + ("f32" if meta16 else "f16"), not meta16, slots), ("layout_" + ("compact" if slots else "slots"), meta16, not slots),
+                    ("meta_f16_layout_slots", True, True)]
+        for vname, v_meta16, v_slots in variants:
+            if (v_meta16, v_slots) == (meta16, slots) or "vggt_stack_" + vname in aux:
+                continue
+            aux["vggt_stack_" + vname] = stack_variant(torch, kvx, w, dev, NL, warm, min(args.steps, 30), v_meta16, v_slots, flops)
         aux["vggt_layer"] = aux_vggt_layer(torch, kvx, si, dev, max(args.steps, 50))
         aux["vggt_long"] = aux_vggt_long(torch, kvx, si, dev, args.long_frames, (100, 250, 500))
         aux["vggt_hires"] = aux_vggt_hires(torch, kvx, si, dev, min(args.steps, 20))

@@ -238,6 +238,15 @@ int kv_stats(kv_handle* h, kv_stats_t* stats);
  * caller; KV_E_RANGE if it is below the cache length. */
 int kv_export(kv_handle* h, int32_t stream, int32_t layer, kv_export_t* bufs);
 
+/* Frames of another size for one stream: Sec. 4 feeds images with a maximum edge of 518 pixels, so the token
+ * count n = 1 + R + N of a frame follows the video's aspect ratio (518 x 392 gives 1041, 518 x 294 gives 782) and
+ * is a property of the stream.  tokens_per_frame: n of this stream, n_special <= n <= kv_config.tokens_per_frame
+ * (which sizes every buffer).  Every quantity of Sec. 3.2 follows the stream's n: T_first = T_current = n,
+ * k = L_max - 2 n, N_pooled = n_special + ceil((n - n_special) / g).  Allowed only while the stream's caches are
+ * empty (KV_E_STATE otherwise; kv_reset first).  A kv_step_batched call carries streams of one frame size
+ * (KV_E_INVAL otherwise).  Host bookkeeping only. */
+int kv_set_stream_tokens(kv_handle* h, int32_t stream, int32_t tokens_per_frame);
+
 /* Forget the contents of one cache (stream, layer), or of all with stream = layer = -1: the
  * next frame is again the first frame of its stream, the one Sec. 3.2 never prunes.  Host
  * bookkeeping only; the caller orders it after the steps already enqueued on that cache. */
@@ -280,7 +289,8 @@ int kv_set_timing(kv_handle* h, uint32_t kernel_mask);
 int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches);
 
 /* Tuning knobs (not needed for correct results):
- *   "attention_splits"            0 = choose automatically, 1..16 = key-range splits
+ *   "attention_splits"            0 = choose automatically, 1..16 = key-range splits (never more than the
+ *                                 partial-result buffers, sized in kv_init for the automatic choice, hold)
  *   "attention_target_workgroups" workgroups the automatic choice aims for
  *   "timing_every"                n >= 1 (default 1): kv_set_timing brackets the launches of every n-th
  *                                 step call only; the event pairs cost a few microseconds of stream

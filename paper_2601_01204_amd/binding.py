@@ -77,6 +77,7 @@ def load_library():
     lib.kv_stats.argtypes = [P, C.POINTER(KvStats)]
     lib.kv_export.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(KvExport)]
     lib.kv_reset.argtypes = [P, C.c_int32, C.c_int32]
+    lib.kv_set_stream_tokens.argtypes = [P, C.c_int32, C.c_int32]
     lib.kv_import.argtypes = [P, C.c_int32, C.c_int32, C.POINTER(KvExport)]
     lib.kv_destroy.argtypes = [P]
     lib.kv_destroy.restype = None
@@ -87,7 +88,7 @@ def load_library():
     lib.kv_set_option.argtypes = [P, C.c_char_p, C.c_int64]
     lib.kv_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, P, C.POINTER(C.c_double)]
     lib.kv_probe_copy.argtypes = [C.c_int64, C.c_int32, P, C.POINTER(C.c_double)]
-    for name in ("kv_init", "kv_step", "kv_step_frames", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_timing",
+    for name in ("kv_init", "kv_step", "kv_step_frames", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_set_stream_tokens", "kv_set_timing",
                  "kv_read_timing", "kv_set_option", "kv_probe_mfma_bf16", "kv_probe_copy", "kv_import"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -228,6 +229,9 @@ class KvHandle:
             keep.append(a)
             setattr(x, name, a.ctypes.data)
         self._check(self.lib.kv_import(self._h, stream, layer, C.byref(x)))
+
+    def set_stream_tokens(self, stream: int, tokens_per_frame: int):
+        self._check(self.lib.kv_set_stream_tokens(self._h, stream, tokens_per_frame))
 
     def reset(self, stream: int = -1, layer: int = -1):
         self._check(self.lib.kv_reset(self._h, stream, layer))

@@ -103,6 +103,7 @@ struct kv_handle {
   kv_config cfg{};
   Geometry geo{};
   std::vector<CacheState> caches;
+  std::vector<int32_t> stream_n;       // tokens per frame of each stream (kv_set_stream_tokens; default: tokens_per_frame)
   std::vector<int64_t> seen_in_call;   // per cache: the step call that last named it (duplicate check without a per-call allocation)
   int64_t call_id = 0;
   uint8_t* arena = nullptr;
@@ -111,7 +112,7 @@ struct kv_handle {
   float* part_o = nullptr;
   float* part_ml = nullptr;
   int64_t bytes_arena = 0, bytes_scratch = 0, bytes_part = 0;
-  int32_t slots_cap = 0;
+  int64_t part_rows_cap = 0;  // (cache, split) slots x padded query rows the partial-result buffers hold
   int32_t splits_override = 0;
   int32_t n_cus = 256;        // compute units of the device (an attention workgroup occupies one by itself)
   int32_t target_wgs = 192;   // three quarters of the CUs: the rest runs the cache-update chain beside attention
@@ -307,9 +308,7 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
     set_query_tiling(g, f * g.n);
     n_pad_max = std::max(n_pad_max, g.n_pad);
   }
-  int qtiles_one = 0;
   set_query_tiling(g, g.n);
-  qtiles_one = g.n_qtiles;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / std::sqrt((float)kHeadDim);
   g.scale_log2 = scale * 1.4426950408889634f;
   g.inv_scale_log2 = 1.0f / g.scale_log2;
@@ -363,19 +362,28 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
   const int64_t n_caches = (int64_t)c.n_streams * c.n_layers;
   h->caches.assign((size_t)n_caches, CacheState());
   h->seen_in_call.assign((size_t)n_caches, 0);
-  h->slots_cap = 0;
-  for (int items = 1; items <= std::min<int64_t>(kMaxItems, n_caches); ++items) {
-    // the most splits pick_splits can choose for this many items when it aims at every compute unit
-    const int64_t base = (int64_t)items * g.H * qtiles_one;      // fewest workgroup columns a call can have
-    const int cap = (int)std::min<int64_t>(kMaxSplits, std::max<int64_t>(4, 2 * (int64_t)cus / base));
-    h->slots_cap = std::max(h->slots_cap, items * cap);
+  h->stream_n.assign((size_t)c.n_streams, c.tokens_per_frame);
+  // Partial results of the key-range splits: room for the largest (caches per launch) x (splits) x (padded query rows)
+  // the automatic choice can reach, found by running it over every launch shape this handle can see.
+  int64_t rows_cap = 0;
+  for (int f = 1; f <= h->f_max; ++f) {
+    Geometry gf = g;
+    set_query_tiling(gf, f * g.n);
+    const int tiles_max = (g.t_cap + kTileK - 1) / kTileK + (gf.n_new + kTileK - 1) / kTileK;
+    for (int items = 1; items <= std::min<int64_t>(kMaxItems, n_caches); ++items)
+      for (int tiles = tiles_max; tiles >= 1; tiles = tiles > 1 ? (tiles + 1) / 2 : 0)
+        for (int target : {h->target_wgs, cus}) {
+          const int sp = pick_splits(h, gf, items, tiles, target);
+          rows_cap = std::max(rows_cap, (int64_t)items * sp * gf.n_pad);
+        }
   }
-  h->slots_cap = std::max(h->slots_cap, (int32_t)kMaxSplits);
+  set_query_tiling(g, g.n);
+  h->part_rows_cap = rows_cap;
   h->bytes_arena = n_caches * L.cache_bytes;
   h->bytes_scratch = n_caches * S.bytes;
   h->n_pad_max = n_pad_max;
-  const int64_t part_o_bytes = (int64_t)h->slots_cap * g.H * n_pad_max * kHeadDim * 4;
-  const int64_t part_ml_bytes = (int64_t)h->slots_cap * g.H * n_pad_max * 2 * 4;
+  const int64_t part_o_bytes = rows_cap * g.H * kHeadDim * 4;
+  const int64_t part_ml_bytes = rows_cap * g.H * 2 * 4;
   h->bytes_part = part_o_bytes + part_ml_bytes;
 
   hipError_t e1 = hipMalloc((void**)&h->arena, (size_t)h->bytes_arena);
@@ -414,14 +422,24 @@ int kv_init(const kv_config* cfg, kv_handle** out) {
 namespace {
 
 // One set of launches per group of up to kMaxItems caches.  part_o / part_ml: where the attention
-// kernel's key-range splits leave their partial results, room for slots_cap (cache, split) pairs.
+// kernel's key-range splits leave their partial results, room for rows_cap rows: (cache, split) pairs x padded query rows.
 // with_timing = false: no event is created or recorded by this call.
 int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t n_frames, int64_t tok_stride, int64_t head_stride,
-              void* hip_stream, float* part_o, float* part_ml, int32_t slots_cap, bool with_timing) {
+              void* hip_stream, float* part_o, float* part_ml, int64_t rows_cap, bool with_timing) {
   if (n_items < 1 || !items) return fail(h, KV_E_INVAL, "kv_step: no items");
   const kv_config& c = h->cfg;
   if (n_frames < 1 || n_frames > h->f_max) return fail(h, KV_E_RANGE, "kv_step: %d frames in one call, the handle takes 1..%d (max_frames_per_step)", n_frames, h->f_max);
   Geometry g0 = h->geo;
+  {
+    // the frame size of this call: that of the items' streams, which must agree
+    const int n_call = (items[0].stream >= 0 && items[0].stream < c.n_streams) ? h->stream_n[(size_t)items[0].stream] : g0.n;
+    for (int i = 1; i < n_items; ++i)
+      if (items[i].stream >= 0 && items[i].stream < c.n_streams && h->stream_n[(size_t)items[i].stream] != n_call)
+        return fail(h, KV_E_INVAL, "kv_step: item %d: its stream has %d tokens per frame, item 0's has %d; one call carries frames of one size",
+                    i, h->stream_n[(size_t)items[i].stream], n_call);
+    g0.n = n_call;
+    g0.n_pooled = g0.n_special + (n_call - g0.n_special + g0.pool_group - 1) / g0.pool_group;
+  }
   set_query_tiling(g0, n_frames * g0.n);
   const int n_new = g0.n_new;
   const bool update_first = c.order == KV_PRUNE_THEN_ATTEND;
@@ -488,7 +506,8 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
     const bool beside = h->overlap && h->side && !g0.uncompressed && !update_first &&
                         (int64_t)cnt * g0.H * g0.n_qtiles <= (int64_t)h->n_cus;
     b.g.n_splits = pick_splits(h, b.g, cnt, min_tiles, (beside || h->target_explicit) ? h->target_wgs : h->n_cus);
-    if (cnt * b.g.n_splits > slots_cap) b.g.n_splits = std::max(1, slots_cap / cnt);
+    // never more splits than the partial-result buffers hold (an explicit "attention_splits" may ask for more)
+    b.g.n_splits = (int32_t)std::max<int64_t>(1, std::min<int64_t>(b.g.n_splits, rows_cap / ((int64_t)cnt * b.g.n_pad)));
 
     hipStream_t sb = st;          // stream of the cache-update chain
     if (beside) {
@@ -585,7 +604,7 @@ extern "C" {
 
 int kv_step_batched(kv_handle* h, int32_t n_items, const kv_step_item* items, int64_t tok_stride, int64_t head_stride, void* hip_stream) {
   if (!h) return KV_E_INVAL;
-  return step_impl(h, n_items, items, 1, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->slots_cap, true);
+  return step_impl(h, n_items, items, 1, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->part_rows_cap, true);
 }
 
 int kv_step_frames(kv_handle* h, int32_t stream, int32_t layer, int32_t n_frames, const void* q, const void* k, const void* v,
@@ -598,7 +617,7 @@ int kv_step_frames(kv_handle* h, int32_t stream, int32_t layer, int32_t n_frames
   it.k = k;
   it.v = v;
   it.out = out;
-  return step_impl(h, 1, &it, n_frames, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->slots_cap, true);
+  return step_impl(h, 1, &it, n_frames, tok_stride, head_stride, hip_stream, h->part_o, h->part_ml, h->part_rows_cap, true);
 }
 
 int kv_step_static(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v, int64_t tok_stride,
@@ -621,7 +640,7 @@ int kv_step_static(kv_handle* h, int32_t stream, int32_t layer, const void* q, c
   it.k = k;
   it.v = v;
   it.out = out;
-  return step_impl(h, 1, &it, 1, tok_stride, head_stride, hip_stream, part_o, part_ml, (int32_t)slots, false);
+  return step_impl(h, 1, &it, 1, tok_stride, head_stride, hip_stream, part_o, part_ml, slots * g.n_pad, false);
 }
 
 int kv_step(kv_handle* h, int32_t stream, int32_t layer, const void* q, const void* k, const void* v, int64_t tok_stride,
@@ -782,7 +801,8 @@ int kv_import(kv_handle* h, int32_t stream, int32_t layer, const kv_export_t* x)
     return fail(h, KV_E_INVAL, "kv_import: ids, codes, scales and zero-points must all be given");
   const int T = x->cache_len;
   if (x->frames_seen < 0 || T < 0 || T > g.budget) return fail(h, KV_E_RANGE, "kv_import: cache_len %d / frames_seen %d out of range", T, x->frames_seen);
-  if ((int64_t)T != std::min<int64_t>((int64_t)x->frames_seen * g.n, g.budget))
+  const int64_t n_stream = h->stream_n[(size_t)stream];
+  if ((int64_t)T != std::min<int64_t>((int64_t)x->frames_seen * n_stream, g.budget))
     return fail(h, KV_E_INVAL, "kv_import: cache_len %d is not min(frames_seen * tokens_per_frame, budget_tokens)", T);
   const int H = g.H;
   const int G = (T + g.k_group - 1) / g.k_group;
@@ -869,7 +889,7 @@ int kv_import(kv_handle* h, int32_t stream, int32_t layer, const kv_export_t* x)
   cs.t_c = T;
   cs.cur = 0;
   cs.frames = x->frames_seen;
-  cs.dropped = (int64_t)x->frames_seen * g.n - T;
+  cs.dropped = (int64_t)x->frames_seen * n_stream - T;
   h->caches[ci] = cs;
   return KV_OK;
 }
@@ -883,6 +903,19 @@ int kv_reset(kv_handle* h, int32_t stream, int32_t layer) {
   }
   if (stream < 0 || stream >= c.n_streams || layer < 0 || layer >= c.n_layers) return fail(h, KV_E_RANGE, "kv_reset: stream/layer out of range");
   h->caches[(size_t)stream * c.n_layers + layer] = CacheState();
+  return KV_OK;
+}
+
+int kv_set_stream_tokens(kv_handle* h, int32_t stream, int32_t tokens_per_frame) {
+  if (!h) return KV_E_INVAL;
+  const kv_config& c = h->cfg;
+  if (stream < 0 || stream >= c.n_streams) return fail(h, KV_E_RANGE, "kv_set_stream_tokens: stream out of range");
+  if (tokens_per_frame < 1 || tokens_per_frame > c.tokens_per_frame || tokens_per_frame < c.n_special)
+    return fail(h, KV_E_RANGE, "kv_set_stream_tokens: tokens_per_frame must be in [max(1, n_special), %d]", c.tokens_per_frame);
+  for (int l = 0; l < c.n_layers; ++l)
+    if (h->caches[(size_t)stream * c.n_layers + l].frames != 0)
+      return fail(h, KV_E_STATE, "kv_set_stream_tokens: stream %d has frames in its caches; kv_reset it first", stream);
+  h->stream_n[(size_t)stream] = tokens_per_frame;
   return KV_OK;
 }
 

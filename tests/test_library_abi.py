@@ -20,7 +20,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     lib = kvx.load_library()
     names = _declared_functions()
-    assert {"kv_init", "kv_step", "kv_step_frames", "kv_step_static", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_destroy",
+    assert {"kv_init", "kv_step", "kv_step_frames", "kv_step_static", "kv_set_stream_tokens", "kv_step_batched", "kv_stats", "kv_export", "kv_reset", "kv_destroy",
             "kv_last_error", "kv_set_timing", "kv_read_timing", "kv_set_option", "kv_import", "kv_probe_mfma_bf16",
             "kv_probe_copy"} <= set(names)
     for name in names:
