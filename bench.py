@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel come from a rocprofv3 --pmc run whose summary and figures are
 # tracked in profiles/; the file names the sources it was measured on, and a stale file yields traffic = null.
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attn_kernel_vggt_stack_traffic.json")
-KERNEL_SOURCES = ("attn.hip", "attn16.hip", "kvx_api.hip", "kvx_dev.h")
+KERNEL_SOURCES = ("attn.hip", "attn16.hip", "kvx_dev.h")
 
 
 def kernel_source_hash() -> str:
@@ -263,6 +263,28 @@ def aux_vggt_layer(torch, kvx, si, dev, steps):
     return out
 
 
+def aux_small_budgets(torch, kvx, si, dev, steps):
+    """The paper's own cache budgets (L_max = 2K in its experiments, 2K-8K in its ablation) on one layer cache:
+    the step is then bound by the launch latencies of the update chain rather than by any roofline.  L = 2048
+    needs frames of at most 1024 tokens (first and current frame are always kept), so it runs on 518 x 294 frames
+    (782 tokens); 4096 and 8192 on 518 x 392 frames (1041 tokens)."""
+    import dataclasses
+    out = {}
+    base = si.WORKLOADS["vggt_layer"]
+    for n, L in ((782, 2048), (1041, 4096), (1041, 8192)):
+        w = dataclasses.replace(base, tokens_per_frame=n, budget_tokens=L)
+        for meta16 in (False, True):
+            run = StackRun(torch, kvx, w, dev, 1, 1, 12, 107, meta_format=kvx.KV_META_F16 if meta16 else kvx.KV_META_F32)
+            run.run(-(-L // n) + 3)
+            dt = run.timed(steps)
+            us = kernel_times(run, min(steps, 50))
+            out[f"n{n}_L{L}_meta_{'f16' if meta16 else 'f32'}"] = {
+                "frames/s": round(steps / dt, 1), "us_per_step": round(dt * 1e6 / steps, 1),
+                "kernel_us": {k: round(v, 2) for k, v in us.items()}}
+            run.close()
+    return out
+
+
 def aux_vggt_long(torch, kvx, si, dev, frames_total, unc_marks):
     """Fourth configuration: 24 layers streamed for frames_total frames with the compressed cache (per-frame time
     and allocated bytes sampled along the way), against the uncompressed bf16 cache of the same 24 layers at the
@@ -345,7 +367,7 @@ def main():
     ap.add_argument("--long-frames", type=int, default=1000, help="frames of the long-stream run in aux")
     ap.add_argument("--layout", choices=("compact", "slots"), default="compact",
                     help="cache layout of the headline run: compacting double buffer, or slot-stable single buffer")
-    ap.add_argument("--meta", choices=("f32", "f16"), default="f32",
+    ap.add_argument("--meta", choices=("f32", "f16"), default="f16",
                     help="quantiser metadata format of the headline run: fp32 scale + int32 zero-point, or 16-bit scale + zero-point")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 1 GiB device-to-device copies (copy_probe_kernel), the known-size reference for HBM byte counters")
@@ -437,6 +459,7 @@ def main():
                 continue
             aux["vggt_stack_" + vname] = stack_variant(torch, kvx, w, dev, NL, warm, min(args.steps, 30), v_meta16, v_slots, flops)
         aux["vggt_layer"] = aux_vggt_layer(torch, kvx, si, dev, max(args.steps, 50))
+        aux["small_budgets"] = aux_small_budgets(torch, kvx, si, dev, max(args.steps, 100))
         aux["vggt_long"] = aux_vggt_long(torch, kvx, si, dev, args.long_frames, (100, 250, 500))
         aux["vggt_hires"] = aux_vggt_hires(torch, kvx, si, dev, min(args.steps, 20))
         # what this machine sustains: a register-resident bf16 MFMA loop on every CU (~5 ms per launch,
