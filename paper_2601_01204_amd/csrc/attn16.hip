@@ -129,14 +129,28 @@ __device__ __forceinline__ void pin_qk_steps(std::integer_sequence<int, I...>) {
   ((sched_group<0x100, ((I + AHEAD < 8) ? 1 : 0) + (((I & 1) == 0 && (I >> 1) + 2 < 4) ? 1 : 0)>(), sched_group<0x008, 1>()), ...);
 }
 
+// Linear block id -> (column, query tile), column = (item, split, head).  Workgroups go to the 8 XCDs round-robin by
+// id and each XCD has its own L2, so the query tiles of one column, which read the same K/V codes, get ids that are
+// multiples of 8 apart and next to each other in dispatch order: they run on one XCD at about the same time and the
+// second and third read of a tile is served by that XCD's L2 instead of HBM.  Columns are taken in groups of 8 (the
+// last group may be smaller): id = group * 8 * n_qtiles + qt * group_size + (column within the group).
+__device__ __forceinline__ void decode_block(int bid, int n_cols, int n_qtiles, int& col, int& qt) {
+  const int per_group = 8 * n_qtiles;
+  const int grp = bid / per_group;
+  const int rest = bid - grp * per_group;
+  const int gsize = min(8, n_cols - grp * 8);
+  qt = rest / gsize;
+  col = grp * 8 + (rest - qt * gsize);
+}
+
 template <int KB, int VB>
 __global__ __launch_bounds__(kAttnMaxWaves * 64) void attn16_kernel(const KvxBatch b) {
   const Geometry& g = b.g;
-  int bid = blockIdx.x;
+  int bid, qt;
+  decode_block(blockIdx.x, g.H * g.n_splits * b.n_items, g.n_qtiles, bid, qt);
   const int h = bid % g.H; bid /= g.H;
   const int split = bid % g.n_splits; bid /= g.n_splits;
-  const int item_idx = bid % b.n_items; bid /= b.n_items;
-  const int qt = bid;
+  const int item_idx = bid;
   const Item it = b.items[item_idx];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
