@@ -363,6 +363,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--splits", type=int, default=0, help="override the attention key-range split count")
     ap.add_argument("--no-overlap", action="store_true", help="run the cache update after attention instead of beside it")
+    ap.add_argument("--overlap", type=int, default=None, choices=(0, 1, 2),
+                    help="the library's overlap_update option: 0 in order, 1 the library's choice (default), 2 always beside")
     ap.add_argument("--no-aux", action="store_true", help="skip the other configurations (one layer, long stream, high-resolution multi-stream)")
     ap.add_argument("--long-frames", type=int, default=1000, help="frames of the long-stream run in aux")
     ap.add_argument("--layout", choices=("compact", "slots"), default="compact",
@@ -395,6 +397,8 @@ def main():
         run.h.set_option("attention_splits", args.splits)
     if args.no_overlap:
         run.h.set_option("overlap_update", 0)
+    elif args.overlap is not None:
+        run.h.set_option("overlap_update", args.overlap)
     fill = -(-L // n) + 1                       # frames until every cache is full and prunes every step
     warm = max(args.warmup, fill)
     run.run(warm)

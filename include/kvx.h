@@ -297,10 +297,13 @@ int kv_read_timing(kv_handle* h, float* total_ms, int32_t* launches);
  *                                 time each, so a benchmark samples them rather than paying them per step
  *   "debug_checks"                1: every step first scans q, k and v for infinities and NaNs
  *                                 and reports them through kv_stats (nonfinite_flag); 0 (default)
- *   "overlap_update"              1 (default): scoring, pruning and re-quantisation run on a
- *                                 second stream of the library beside attention, joined back
- *                                 into hip_stream before kv_step returns; 0: everything in
- *                                 order on hip_stream */
+ *   "overlap_update"              1 (default): when attention alone cannot fill the chip (one or
+ *                                 a few caches per call), scoring, pruning and re-quantisation
+ *                                 run on a second stream of the library next to attention,
+ *                                 joined back into hip_stream before kv_step returns (slot
+ *                                 layout: pooling, scoring and selection do; its writers always
+ *                                 follow attention); 2: the same at any launch size; 0:
+ *                                 everything in order on hip_stream */
 int kv_set_option(kv_handle* h, const char* name, int64_t value);
 
 /* Machine probes (measurement aids, no handle needed; they allocate and free their own

@@ -500,12 +500,18 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
     }
     b.g.part_o = part_o;
     b.g.part_ml = part_ml;
-    // The cache-update chain runs beside attention on the library's second stream when attention alone cannot fill
-    // the chip (fewer workgroup columns than compute units: one or a few caches per call); a launch that fills the
-    // chip several times over gains nothing from sharing it, so there the chain follows attention on the caller's stream.
-    const bool beside = h->overlap && h->side && !g0.uncompressed && !update_first &&
-                        (int64_t)cnt * g0.H * g0.n_qtiles <= (int64_t)h->n_cus;
-    b.g.n_splits = pick_splits(h, b.g, cnt, min_tiles, (beside || h->target_explicit) ? h->target_wgs : h->n_cus);
+    // The cache-update chain runs next to attention on the library's second stream when attention alone cannot fill
+    // the chip (fewer workgroup columns than compute units: one or a few caches per call).  The attention workgroups
+    // of a launch that fills the chip hold every vector register of their compute units, so another kernel's
+    // workgroups only get a unit between two of them: there the chain follows attention on the caller's stream
+    // unless "overlap_update" 2 asks for the second stream at any size.  The slot layout's writers always follow
+    // attention (they update the buffer it reads); "overlap_update" 0, the uncompressed baseline and the update-first
+    // order (attention reads what the update wrote) keep everything in order on the caller's stream.
+    const bool may_overlap = h->overlap != 0 && h->side && !g0.uncompressed && !update_first;
+    const bool small_launch = (int64_t)cnt * g0.H * g0.n_qtiles <= (int64_t)h->n_cus;
+    const bool beside = may_overlap && (h->overlap == 2 || small_launch);
+    // a small launch leaves a quarter of the compute units to the chain next to it
+    b.g.n_splits = pick_splits(h, b.g, cnt, min_tiles, ((beside && small_launch) || h->target_explicit) ? h->target_wgs : h->n_cus);
     // never more splits than the partial-result buffers hold (an explicit "attention_splits" may ask for more)
     b.g.n_splits = (int32_t)std::max<int64_t>(1, std::min<int64_t>(b.g.n_splits, rows_cap / ((int64_t)cnt * b.g.n_pad)));
 
@@ -515,9 +521,9 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
       hipStreamWaitEvent(h->side, h->ev_fork, 0);
       sb = h->side;
     }
-    if (g0.uncompressed) {
-      // the baseline appends in place behind the rows attention reads: same stream, after it
-    } else {
+    // the slot layout is updated in place: its writers follow attention, which reads the same buffer
+    const bool rebuild_after = g0.slots && !update_first;
+    if (!g0.uncompressed) {
       if (any_prune) {
         record(h, KV_K_POOL, true, sb);
         launch_pool(b, sb);
@@ -529,7 +535,7 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
         launch_select(b, max_tc, sb);
         record(h, KV_K_SELECT, false, sb);
       }
-      if (!g0.slots || update_first) {
+      if (!rebuild_after) {
         record(h, KV_K_REBUILD_K, true, sb);
         launch_rebuild_k(b, max_tnew, sb);
         record(h, KV_K_REBUILD_K, false, sb);
@@ -572,8 +578,7 @@ int step_impl(kv_handle* h, int32_t n_items, const kv_step_item* items, int32_t 
       hipEventRecord(h->ev_join, sb);
       hipStreamWaitEvent(st, h->ev_join, 0);
     }
-    if (g0.slots && !update_first) {
-      // the slot layout is updated in place: the writers follow attention, which reads the same buffer
+    if (rebuild_after) {
       record(h, KV_K_REBUILD_K, true, st);
       launch_rebuild_k(b, max_tnew, st);
       record(h, KV_K_REBUILD_K, false, st);
@@ -977,7 +982,8 @@ int kv_set_option(kv_handle* h, const char* name, int64_t value) {
     return KV_OK;
   }
   if (!strcmp(name, "overlap_update")) {
-    h->overlap = value != 0;
+    if (value < 0 || value > 2) return fail(h, KV_E_RANGE, "kv_set_option: overlap_update takes 0..2");
+    h->overlap = (int32_t)value;
     h->target_wgs = h->overlap ? std::max(1, h->n_cus * 3 / 4) : h->n_cus;
     return KV_OK;
   }

@@ -150,6 +150,30 @@ __device__ __forceinline__ void pack16(const int (&code)[16], uint8_t* p) {
   }
 }
 
+// 16 codes (floats holding integers 0 .. 2^B - 1) packed into a row piece: 16-bit halves are built in fp32 (exact:
+// at most 16 bits) by fused multiply-adds, converted once and joined.
+template <int B>
+__device__ __forceinline__ void pack16f(const float (&c)[16], uint8_t* p) {
+  constexpr int kPer = 16 / B;                  // codes per 16-bit half: 8, 4 or 2
+  constexpr float kMul = (float)(1 << B);
+  uint32_t half16[16 / kPer];
+#pragma unroll
+  for (int hh = 0; hh < 16 / kPer; ++hh) {
+    float acc = c[hh * kPer + kPer - 1];
+#pragma unroll
+    for (int e = kPer - 2; e >= 0; --e) acc = __builtin_fmaf(acc, kMul, c[hh * kPer + e]);
+    half16[hh] = (uint32_t)acc;
+  }
+  if constexpr (B == 2) {
+    *reinterpret_cast<uint32_t*>(p) = half16[0] | (half16[1] << 16);
+  } else if constexpr (B == 4) {
+    *reinterpret_cast<uint2*>(p) = make_uint2(half16[0] | (half16[1] << 16), half16[2] | (half16[3] << 16));
+  } else {
+    *reinterpret_cast<uint4*>(p) = make_uint4(half16[0] | (half16[1] << 16), half16[2] | (half16[3] << 16),
+                                              half16[4] | (half16[5] << 16), half16[6] | (half16[7] << 16));
+  }
+}
+
 __device__ __forceinline__ void load_input16(const void* base, int64_t off, int in_f32, float (&x)[16]) {
   if (in_f32) {
     const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + off);
@@ -229,6 +253,7 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
   __shared__ __attribute__((aligned(16))) float gs[2][kHeadDim];
   __shared__ __attribute__((aligned(16))) float gr[2][kHeadDim];     // refined reciprocals of the scales
   __shared__ __attribute__((aligned(16))) int32_t gz[2][kHeadDim];
+  __shared__ __attribute__((aligned(16))) float gzf[2][kHeadDim];    // the zero-points as floats
   __shared__ int unsafe_scales;                                      // some scale needs the plain division
 
   float x[16];
@@ -248,12 +273,25 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
         const uint4 a0 = ap[0], a1 = ap[1], z0 = zp[0], z1 = zp[1];
         const uint32_t aw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
         const uint32_t zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+        // word k of an octet holds channels k and k + 4, and so do the codes once masked: code - z is taken on both
+        // at once as (1024 + code) - (1024 + z) in halves (integers below 2048: exact)
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int pos = meta16_pos(e);                       // half index among the 16
-          const float sv = half_bits_to_f32((aw[pos >> 1] >> (16 * (pos & 1))) & 0xFFFFu) * g.inv_scale_log2;
-          const float zf = half_bits_to_f32((zw[pos >> 1] >> (16 * (pos & 1))) & 0xFFFFu) - 1024.0f;
-          x[e] = sv * ((float)code16<B>(wsrc, e) - zf);
+        for (int o = 0; o < 2; ++o) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            uint32_t cw;
+            if constexpr (B == 4) {
+              cw = (wsrc[o] >> (4 * k)) & 0x000F000Fu;
+            } else {
+              const uint32_t t = (wsrc[0] >> (16 * o + 2 * k)) & 0x0303u;      // codes k and k + 4 of the octet
+              cw = (t | (t << 8)) & 0x00030003u;
+            }
+            const h2 d = __builtin_bit_cast(h2, cw | 0x64006400u) - __builtin_bit_cast(h2, zw[4 * o + k]);
+            const h2 a = __builtin_bit_cast(h2, aw[4 * o + k]);
+            x[8 * o + k] = ((float)a.x * g.inv_scale_log2) * (float)d.x;
+            x[8 * o + k + 4] = ((float)a.y * g.inv_scale_log2) * (float)d.y;
+          }
         }
       } else if (!carried) {
         const int sg = src >> k_shift;
@@ -353,7 +391,8 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
       gs[gi][c] = s;
       gr[gi][c] = dv.r;
       gz[gi][c] = z;
-      if (!dv.safe) unsafe_scales = 1;
+      gzf[gi][c] = (float)z;
+      if (!dv.safe || z >= (1 << 23) || z <= -(1 << 23)) unsafe_scales = 1;      // also: z not exact as a float
       if (SLOTS && group_carried) {
       } else if constexpr (M16) {
         reinterpret_cast<uint16_t*>(nxt + g.lay.k_scale)[moff] = f32_to_half_bits(a16);
@@ -375,26 +414,28 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
       else *reinterpret_cast<uint4*>(dst) = make_uint4(wsrc[0], wsrc[1], wsrc[2], wsrc[3]);
     } else {
       const int gi = r >> k_shift;
-      int code[16];
       if (unsafe_scales) {                      // block-uniform and rare
+        int code[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) code[e] = quant_code(x[e], gs[gi][cb * 16 + e], gz[gi][cb * 16 + e], levels);
+        pack16<B>(code, dst);
       } else {
+        // rint(x / s) + z in floats: the quotient's five fused operations, then an exact integer sum (the rounded
+        // quotient is an integer below 2^24 or the clamp decides; |z| < 2^23 here) clamped by one median.
+        float cf[16];
+        const float flev = (float)levels;
 #pragma unroll
         for (int v4 = 0; v4 < 4; ++v4) {
           const float4 sv = *reinterpret_cast<const float4*>(&gs[gi][cb * 16 + 4 * v4]);
           const float4 rv = *reinterpret_cast<const float4*>(&gr[gi][cb * 16 + 4 * v4]);
-          const int4 zv = *reinterpret_cast<const int4*>(&gz[gi][cb * 16 + 4 * v4]);
-          const float sa[4] = {sv.x, sv.y, sv.z, sv.w}, ra[4] = {rv.x, rv.y, rv.z, rv.w};
-          const int za[4] = {zv.x, zv.y, zv.z, zv.w};
+          const float4 zv = *reinterpret_cast<const float4*>(&gzf[gi][cb * 16 + 4 * v4]);
+          const float sa[4] = {sv.x, sv.y, sv.z, sv.w}, ra[4] = {rv.x, rv.y, rv.z, rv.w}, za[4] = {zv.x, zv.y, zv.z, zv.w};
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int q = (int)rintf(div_fast(x[4 * v4 + k], sa[k], ra[k])) + za[k];
-            code[4 * v4 + k] = min(max(q, 0), levels);
-          }
+          for (int k = 0; k < 4; ++k)
+            cf[4 * v4 + k] = __builtin_amdgcn_fmed3f(rintf(div_fast(x[4 * v4 + k], sa[k], ra[k])) + za[k], 0.f, flev);
         }
+        pack16f<B>(cf, dst);
       }
-      pack16<B>(code, dst);
     }
   }
 }
