@@ -285,13 +285,14 @@ def aux_small_budgets(torch, kvx, si, dev, steps):
     return out
 
 
-def aux_vggt_long(torch, kvx, si, dev, frames_total, unc_marks):
+def aux_vggt_long(torch, kvx, si, dev, frames_total, unc_marks, meta16):
     """Fourth configuration: 24 layers streamed for frames_total frames with the compressed cache (per-frame time
     and allocated bytes sampled along the way), against the uncompressed bf16 cache of the same 24 layers at the
     marks in unc_marks (plain Eq. 1 over every past frame)."""
     w = si.WORKLOADS["vggt_long"]
-    out = {"workload": f"vggt_long: 24 layers x {frames_total} frames, budget 16384, INT4/INT4 g64"}
-    run = StackRun(torch, kvx, w, dev, 1, w.n_layers, 20, 103)
+    out = {"workload": f"vggt_long: 24 layers x {frames_total} frames, budget 16384, INT4/INT4 g64, " +
+           ("16-bit" if meta16 else "fp32 + int32") + " metadata"}
+    run = StackRun(torch, kvx, w, dev, 1, w.n_layers, 20, 103, meta_format=kvx.KV_META_F16 if meta16 else kvx.KV_META_F32)
     marks = sorted({m for m in (1, 100, 250, 500, 1000) if m <= frames_total} | {frames_total})
     comp = {}
     for m in marks:
@@ -332,10 +333,10 @@ def aux_vggt_long(torch, kvx, si, dev, frames_total, unc_marks):
     return out
 
 
-def aux_vggt_hires(torch, kvx, si, dev, steps):
+def aux_vggt_hires(torch, kvx, si, dev, steps, meta16):
     """Fifth configuration: 4 streams x 24 layers, 1374 tokens per frame, budget 24576, INT2 keys g32 / INT4 values."""
     w = si.WORKLOADS["vggt_hires"]
-    run = StackRun(torch, kvx, w, dev, w.n_streams, w.n_layers, 20, 105)
+    run = StackRun(torch, kvx, w, dev, w.n_streams, w.n_layers, 20, 105, meta_format=kvx.KV_META_F16 if meta16 else kvx.KV_META_F32)
     fill = -(-w.budget_tokens // w.tokens_per_frame) + 1
     run.run(fill + 2)
     dt = run.timed(steps)
@@ -343,13 +344,14 @@ def aux_vggt_hires(torch, kvx, si, dev, steps):
     st = run.h.stats()
     launches = 2          # 96 caches = two launches of 48
     per_launch = w.n_streams * w.n_layers / launches
-    out = {"workload": "vggt_hires: 4 streams x 24 layers in one kv_step_batched, 1374 tokens/frame, budget 24576, INT2 K g32 / INT4 V g64",
+    out = {"workload": "vggt_hires: 4 streams x 24 layers in one kv_step_batched, 1374 tokens/frame, budget 24576, INT2 K g32 / INT4 V g64, " +
+                       ("16-bit" if meta16 else "fp32 + int32") + " metadata",
            "frames/s (4-stream x 24-layer frames)": round(steps / dt, 2), "ms_per_step": round(dt * 1e3 / steps, 3),
            "stream_frames/s": round(w.n_streams * steps / dt, 2),
            "attention_TFLOP/s": round(per_launch * attention_flops(w) / (us["attention"] * 1e-6) / 1e12, 1),
            "attention_frac": round(per_launch * attention_flops(w) / (us["attention"] * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS, 4),
            "kernel_us_per_launch_of_48": {k: round(v, 2) for k, v in us.items()},
-           "hbm_kernels": hbm_report(w, per_launch, us),
+           "hbm_kernels": hbm_report(w, per_launch, us, 4 if meta16 else 8),
            "kv_bytes": {"live_per_cache": st["bytes_live_per_cache"], "allocated": st["bytes_allocated"]}}
     run.close()
     return out
@@ -456,16 +458,13 @@ def main():
     if not args.no_aux:
         aux = {}
         # the same 24-layer step in the other quantiser metadata format and in the other layout
-        variants = [("meta_" + ("f32" if meta16 else "f16"), not meta16, slots), ("layout_" + ("compact" if slots else "slots"), meta16, not slots),
-                    ("meta_f16_layout_slots", True, True)]
+        variants = [("meta_" + ("f32" if meta16 else "f16"), not meta16, slots), ("layout_" + ("compact" if slots else "slots"), meta16, not slots)]
         for vname, v_meta16, v_slots in variants:
-            if (v_meta16, v_slots) == (meta16, slots) or "vggt_stack_" + vname in aux:
-                continue
             aux["vggt_stack_" + vname] = stack_variant(torch, kvx, w, dev, NL, warm, min(args.steps, 30), v_meta16, v_slots, flops)
         aux["vggt_layer"] = aux_vggt_layer(torch, kvx, si, dev, max(args.steps, 50))
         aux["small_budgets"] = aux_small_budgets(torch, kvx, si, dev, max(args.steps, 100))
-        aux["vggt_long"] = aux_vggt_long(torch, kvx, si, dev, args.long_frames, (100, 250, 500))
-        aux["vggt_hires"] = aux_vggt_hires(torch, kvx, si, dev, min(args.steps, 20))
+        aux["vggt_long"] = aux_vggt_long(torch, kvx, si, dev, args.long_frames, (100, 250, 500), meta16)
+        aux["vggt_hires"] = aux_vggt_hires(torch, kvx, si, dev, min(args.steps, 20), meta16)
         # what this machine sustains: a register-resident bf16 MFMA loop on every CU (~5 ms per launch,
         # long enough for the clock to settle under the power limit) and a 1 GiB streaming copy
         aux["machine"] = {"mfma_bf16_sustained_TFLOP/s": round(kvx.probe_mfma_bf16(50000, 3), 1),
