@@ -61,6 +61,18 @@ __device__ __forceinline__ void quant_params16_v(float mn, float mx, int levels,
   clipped = c0 || c1;
 }
 
+// fl(float(half) * f) in one instruction: the low / high half of w times the fp32 f (v_fma_mix_f32, addend +0).
+__device__ __forceinline__ float mix_mul_lo(uint32_t w, float f) {
+  float r;
+  asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(f));
+  return r;
+}
+__device__ __forceinline__ float mix_mul_hi(uint32_t w, float f) {
+  float r;
+  asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(f));
+  return r;
+}
+
 __device__ __forceinline__ int quant_code(float x, float s, int32_t z, int levels) {
   const int q = (int)rintf(x / s) + z;
   return min(max(q, 0), levels);
@@ -288,9 +300,13 @@ __global__ __launch_bounds__(256, 8) void rebuild_k_kernel(const KvxBatch b) {
               cw = (t | (t << 8)) & 0x00030003u;
             }
             const h2 d = __builtin_bit_cast(h2, cw | 0x64006400u) - __builtin_bit_cast(h2, zw[4 * o + k]);
-            const h2 a = __builtin_bit_cast(h2, aw[4 * o + k]);
-            x[8 * o + k] = ((float)a.x * g.inv_scale_log2) * (float)d.x;
-            x[8 * o + k + 4] = ((float)a.y * g.inv_scale_log2) * (float)d.y;
+            // s = fl(a * c), then fl(s * d): the mixed-precision multiply-add takes the half operand as it is and
+            // rounds once, like a conversion (exact) followed by a multiply; the +0 addend changes nothing, no
+            // product here is -0 (a, c, s > 0 and a zero difference is +0)
+            const uint32_t aw2 = aw[4 * o + k], dw2 = __builtin_bit_cast(uint32_t, d);
+            const float s0 = mix_mul_lo(aw2, g.inv_scale_log2), s1 = mix_mul_hi(aw2, g.inv_scale_log2);
+            x[8 * o + k] = mix_mul_lo(dw2, s0);
+            x[8 * o + k + 4] = mix_mul_hi(dw2, s1);
           }
         }
       } else if (!carried) {
