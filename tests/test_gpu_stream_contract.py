@@ -36,7 +36,7 @@ def test_two_caches_on_two_streams_ordered_by_events(meta16, slots):
             s = streams[l]
             with torch.cuda.stream(s):
                 # the inputs are uploaded and converted on the step's own stream, right before the call
-                tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0", non_blocking=True).to(torch.bfloat16) for a in (q, k, v))
+                tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0").to(torch.bfloat16) for a in (q, k, v))
                 out = torch.empty(tq.shape, dtype=torch.float32, device="cuda:0")
                 if last is not None:
                     s.wait_event(last)            # the contract: calls on one handle are ordered with each other
